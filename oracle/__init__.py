@@ -1,0 +1,124 @@
+"""CPU oracle of the PacTrain compression path (test infrastructure only).
+
+Thin ctypes wrapper around ``pac_oracle.cpp``: numpy arrays in, numpy arrays out.
+Nothing here is used by the product; the GPU library shares no code with it.
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pac_oracle.cpp")
+_LIB = os.path.join(_HERE, "libpac_oracle.so")
+
+F32 = 0
+BF16 = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with the host compiler (no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-std=c++17", "-O2", "-fno-fast-math", "-ffp-contract=off", "-fPIC", "-shared",
+               "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        u64, u32, i32, vp = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p
+        lib.orc_keep_count.restype = u64
+        lib.orc_keep_count.argtypes = [u64, ctypes.c_double]
+        lib.orc_build_mask.restype = i32
+        lib.orc_build_mask.argtypes = [vp, u64, vp, u32, vp, vp, vp, vp]
+        lib.orc_compress.restype = u64
+        lib.orc_compress.argtypes = [vp, i32, u64, vp, vp, u64]
+        lib.orc_reduce.restype = None
+        lib.orc_reduce.argtypes = [vp, u32, i32, u64, vp]
+        lib.orc_decompress.restype = u64
+        lib.orc_decompress.argtypes = [vp, i32, u64, vp, vp, u64]
+        lib.orc_f32_to_bf16.restype = None
+        lib.orc_f32_to_bf16.argtypes = [vp, vp, u64]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray) -> int:
+    return a.ctypes.data
+
+
+def _elem_dtype(dtype: int):
+    return np.float32 if dtype == F32 else np.uint16
+
+
+def keep_count(n: int, sparsity: float) -> int:
+    return int(_load().orc_keep_count(int(n), float(sparsity)))
+
+
+def mask_words(n: int) -> int:
+    return (int(n) + 63) // 64
+
+
+def build_mask(weights: np.ndarray, seg_offsets=None, sparsity=0.0):
+    """Return (mask uint64[ceil(n/64)], prefix uint32[ceil(n/64)], nnz)."""
+    w = np.ascontiguousarray(weights, dtype=np.float32).reshape(-1)
+    n = w.size
+    if seg_offsets is None:
+        seg_offsets = [0, n]
+    off = np.ascontiguousarray(seg_offsets, dtype=np.uint64)
+    nseg = off.size - 1
+    sp = np.ascontiguousarray(np.broadcast_to(np.asarray(sparsity, dtype=np.float64), (nseg,)))
+    words = mask_words(n)
+    mask = np.zeros(max(words, 1), dtype=np.uint64)[:words]
+    prefix = np.zeros(max(words, 1), dtype=np.uint32)[:words]
+    nnz = ctypes.c_uint64(0)
+    rc = _load().orc_build_mask(_ptr(w), n, _ptr(off), nseg, _ptr(sp), _ptr(mask), _ptr(prefix),
+                                ctypes.addressof(nnz))
+    if rc != 0:
+        raise ValueError("orc_build_mask: bad arguments")
+    return mask, prefix, int(nnz.value)
+
+
+def compress(grad: np.ndarray, mask: np.ndarray, nnz: int, dtype: int = F32) -> np.ndarray:
+    g = np.ascontiguousarray(grad, dtype=_elem_dtype(dtype)).reshape(-1)
+    out = np.empty(nnz, dtype=_elem_dtype(dtype))
+    got = _load().orc_compress(_ptr(g), dtype, g.size, _ptr(np.ascontiguousarray(mask)), _ptr(out), nnz)
+    if got != nnz:
+        raise ValueError(f"mask holds {got} set bits, caller said {nnz}")
+    return out
+
+
+def reduce_local(bufs, dtype: int = F32) -> np.ndarray:
+    arrs = [np.ascontiguousarray(b, dtype=_elem_dtype(dtype)).reshape(-1) for b in bufs]
+    nnz = arrs[0].size
+    assert all(a.size == nnz for a in arrs)
+    ptrs = (ctypes.c_void_p * len(arrs))(*[_ptr(a) for a in arrs])
+    out = np.empty(nnz, dtype=_elem_dtype(dtype))
+    _load().orc_reduce(ctypes.addressof(ptrs), len(arrs), dtype, nnz, _ptr(out))
+    return out
+
+
+def decompress(compact: np.ndarray, mask: np.ndarray, n: int, dtype: int = F32) -> np.ndarray:
+    c = np.ascontiguousarray(compact, dtype=_elem_dtype(dtype)).reshape(-1)
+    out = np.empty(n, dtype=_elem_dtype(dtype))
+    used = _load().orc_decompress(_ptr(c), dtype, c.size, _ptr(np.ascontiguousarray(mask)), _ptr(out), n)
+    if used != c.size:
+        raise ValueError(f"mask holds {used} set bits, compact buffer has {c.size}")
+    return out
+
+
+def f32_to_bf16(x: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    out = np.empty(a.size, dtype=np.uint16)
+    _load().orc_f32_to_bf16(_ptr(a), _ptr(out), a.size)
+    return out
