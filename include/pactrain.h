@@ -1,0 +1,129 @@
+/* pactrain.h - C ABI of the PacTrain per-step gradient compression path on one AMD GPU.
+ *
+ * The path (paper Sec. III-B/III-C, Alg. 1): a pruning mask derived from weight magnitudes is
+ * known to every data-parallel worker; each worker uses it to pack its flat gradient into a
+ * shorter dense buffer; the packed buffers are summed by an ordinary floating-point all-reduce
+ * (the sum of Eq. 1); the reduced buffer is scattered back into a dense gradient whose pruned
+ * positions are zero (Eq. 2).  This library holds the four operations as GPU kernels:
+ *
+ *     pac_build_mask -> pac_compress (once per worker) -> pac_reduce_local -> pac_decompress
+ *
+ * Conventions
+ *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller owns every data
+ *    buffer.  The context owns only scratch (histograms, candidate lists, scan state), sized in
+ *    pac_create; no call on the path allocates.
+ *  - Every path call enqueues its kernels on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream) and returns without synchronising.  Calls on one context must be issued
+ *    on one stream at a time: they share the context's scratch.
+ *  - A call returns PAC_OK or a negative pac_status; argument errors are found on the host before
+ *    anything is launched and leave the outputs untouched.  The text of the last error is kept in
+ *    the context (pac_last_error).  Nothing throws or aborts.
+ *  - Layout: bit b of mask word j stands for flat element 64*j + b; bits at or beyond n in the last
+ *    word are zero.  prefix[j] is the number of set bits in words 0..j-1 over the whole flat set,
+ *    so the element at set bit b of word j lives in compact slot
+ *    prefix[j] + popcount(mask[j] & ((1 << b) - 1)): ascending flat index.
+ *  - Data buffers need element alignment only (4 bytes for PAC_F32, 2 for PAC_BF16); buffers
+ *    aligned to 16 bytes take the wide-access kernels.  d_mask needs 8-byte, d_prefix 4-byte
+ *    alignment.
+ *  - Limits: n < 2^32 elements, at most PAC_MAX_WORKERS buffers per reduction.
+ */
+#ifndef PACTRAIN_H
+#define PACTRAIN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t pac_status;
+enum {
+    PAC_OK = 0,
+    PAC_ERR_ARG = -1,   /* NULL pointer, bad dtype, bad segment table                         */
+    PAC_ERR_ALIGN = -2, /* pointer not aligned to its element size                            */
+    PAC_ERR_RANGE = -3, /* n >= 2^32 or > context capacity, sparsity outside [0,1], W out of range */
+    PAC_ERR_COUNT = -4, /* nnz passed does not fit n                                          */
+    PAC_ERR_HIP = -5,   /* a HIP runtime call failed; pac_last_error holds its text           */
+    PAC_ERR_NOMEM = -6  /* scratch allocation failed in pac_create                            */
+};
+
+typedef enum { PAC_F32 = 0, PAC_BF16 = 1 } pac_dtype;
+
+#define PAC_MAX_WORKERS 64u
+
+typedef struct pac_ctx pac_ctx;
+
+/* Create a context on HIP device `hip_device` able to build masks over up to `max_elems` flat
+ * elements split into up to `max_segments` prune scopes.  Allocates all scratch.  *out is NULL on
+ * failure. */
+pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_t max_segments);
+
+/* Synchronises the device and frees the scratch.  NULL is accepted. */
+pac_status pac_destroy(pac_ctx* ctx);
+
+/* Text of the last error of this context ("" if none).  Owned by the context.  With ctx == NULL,
+ * the text of the last failed pac_create of this thread. */
+const char* pac_last_error(const pac_ctx* ctx);
+
+/* Keep count of one prune scope of n elements at a target sparsity (the pruning ratio of Alg. 1):
+ * k = ceil((1 - s) * n), evaluated in integers with s rounded to the nearest 1e-6.  Pure host
+ * arithmetic; the same rule pac_build_mask applies to each segment.  Returns 0 for s outside
+ * [0,1]. */
+uint64_t pac_keep_count(uint64_t n, double sparsity);
+
+/* Number of 64-bit mask words (and of prefix entries) for n elements: ceil(n / 64). */
+uint64_t pac_mask_words(uint64_t n);
+
+/* (1) Magnitude-pruning mask (paper Sec. II-B: importance = |weight|; Sec. III-B: the selection is a
+ * function of the weights alone, hence identical on all workers; Sec. III-C step 1 / Alg. 1 Prune).
+ *
+ * The flat weights d_weights[0..n) are split into nseg prune scopes [h_seg_offsets[s],
+ * h_seg_offsets[s+1]) (h_seg_offsets[0] = 0, [nseg] = n, ascending, empty scopes allowed); scope s
+ * keeps k_s = pac_keep_count(len_s, h_sparsity[s]) elements: those first in the order
+ * "|w| descending, flat index ascending", where |w| is compared through the bit pattern with the
+ * sign cleared (so -0 ties +0, denormals count, NaN ranks above infinity).  nseg = 1 is a global
+ * prune, one segment per tensor a per-layer prune.  Weights are not modified.
+ *
+ * Writes d_mask[ceil(n/64)] and d_prefix[ceil(n/64)]; *h_nnz_out (may be NULL) receives
+ * sum_s k_s, which is known on the host without waiting for the device.  n = 0 is allowed
+ * (nothing is written). */
+pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n,
+                          const uint64_t* h_seg_offsets, uint32_t nseg, const double* h_sparsity,
+                          uint64_t* d_mask, uint32_t* d_prefix, uint64_t* h_nnz_out,
+                          void* hip_stream);
+
+/* (2) Compress one worker's flat gradient (paper Sec. I / III-B: the shared mask reformats the
+ * sparse gradient into a low-dimensional dense tensor; Alg. 1 compress(update)):
+ * d_compact[slot(i)] = d_grad[i] for every set bit i, bit-exact copies, ascending flat index.
+ * nnz must be the number of set bits (the value pac_build_mask returned); the kernel never writes
+ * at or beyond d_compact[nnz]. */
+pac_status pac_compress(pac_ctx* ctx, const void* d_grad, pac_dtype dtype, uint64_t n,
+                        const uint64_t* d_mask, const uint32_t* d_prefix,
+                        void* d_compact, uint64_t nnz, void* hip_stream);
+
+/* (3) Element-wise sum of W compact buffers held in this GPU's memory: the payload arithmetic of
+ * the all-reduce over workers (the sum in Eq. 1; no 1/n, no learning rate).
+ * out[j] = (((c_0[j] + c_1[j]) + c_2[j]) + ... + c_{W-1}[j]) in IEEE single precision, in that
+ * order.  PAC_BF16: every input is widened to single, the same adds, one round-to-nearest-even
+ * back to bf16 (NaN stays NaN).  h_d_compact is a HOST array of W device pointers, read before
+ * the call returns.  d_out may alias one of the inputs.  1 <= W <= PAC_MAX_WORKERS. */
+pac_status pac_reduce_local(pac_ctx* ctx, const void* const* h_d_compact, uint32_t W,
+                            pac_dtype dtype, uint64_t nnz, void* d_out, void* hip_stream);
+
+/* (4) Decompress (paper Eq. 2 read as a selection): d_dense_out[i] = d_compact[slot(i)] where the
+ * mask bit is set, the all-zero bit pattern (+0.0) elsewhere.  Every one of the n outputs is
+ * written.  No read at or beyond d_compact[nnz]. */
+pac_status pac_decompress(pac_ctx* ctx, const void* d_compact, pac_dtype dtype, uint64_t nnz,
+                          const uint64_t* d_mask, const uint32_t* d_prefix,
+                          void* d_dense_out, uint64_t n, void* hip_stream);
+
+/* Test hook: lower the capacity of the candidate list pac_build_mask uses between its selection
+ * passes (elements; clamped to what pac_create allocated).  Scopes whose candidates do not fit take
+ * the slower in-place selection; results are identical.  Exists so that tests can reach that branch
+ * with small inputs. */
+pac_status pac_debug_set_candidate_capacity(pac_ctx* ctx, uint64_t capacity);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PACTRAIN_H */

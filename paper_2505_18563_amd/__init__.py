@@ -1,0 +1,11 @@
+"""MI355X-native PacTrain compression path: mask -> compress -> sum over workers -> decompress.
+
+The work is done by libpactrain.so (hand-written HIP kernels behind the C ABI of
+include/pactrain.h).  This package only marshals arguments: torch tensors supply device memory
+and streams.  There is no CPU or eager fallback; a missing library is an error.
+"""
+from .binding import (  # noqa: F401
+    PAC_BF16, PAC_F32, PacError, PacContext, library_path, load_library,
+    pac_build_mask, pac_compress, pac_create, pac_debug_set_candidate_capacity, pac_decompress,
+    pac_destroy, pac_keep_count, pac_last_error, pac_mask_words, pac_reduce_local,
+)

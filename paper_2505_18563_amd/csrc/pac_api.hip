@@ -1,0 +1,351 @@
+// C ABI of libpactrain: argument checks, scratch ownership, segment-table upload, launches.
+#include "../../include/pactrain.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "pac_internal.h"
+
+namespace {
+
+constexpr int kRing = 4;               // pinned staging slots for the segment table
+constexpr uint32_t kMaxSegments = 65535;   // scopes index a grid dimension
+constexpr uint64_t kScanTileWords = 2048;  // must match the scan kernels' tile
+
+thread_local char g_create_error[256] = "";
+
+}  // namespace
+
+struct pac_ctx {
+    int device = 0;
+    int num_cu = 0;
+    uint64_t max_elems = 0;
+    uint32_t max_segments = 0;
+    pac::MaskScratch scratch{};
+    uint32_t cand_cap_alloc = 0;
+    // segment table staging
+    pac::SegDesc* h_ring[kRing] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t ring_event[kRing] = {nullptr, nullptr, nullptr, nullptr};
+    bool ring_used[kRing] = {false, false, false, false};
+    int ring_next = 0;
+    std::vector<pac::SegDesc> last_table;   // what the device table currently holds
+    bool table_valid = false;
+    char err[256] = "";
+};
+
+namespace {
+
+pac_status fail(pac_ctx* ctx, pac_status code, const char* fmt, ...) {
+    char* dst = ctx ? ctx->err : g_create_error;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 256, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+// Makes the context's device current for the duration of a call and restores the caller's.
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    hipError_t status = hipSuccess;
+    explicit DeviceGuard(int want) {
+        status = hipGetDevice(&prev);
+        if (status == hipSuccess && prev != want) {
+            status = hipSetDevice(want);
+            switched = status == hipSuccess;
+        }
+    }
+    ~DeviceGuard() {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+bool is_aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+uint32_t elem_size(pac_dtype dt) { return dt == PAC_F32 ? 4u : 2u; }
+
+void free_scratch(pac_ctx* ctx) {
+    pac::MaskScratch& s = ctx->scratch;
+    (void)hipFree(s.seg);
+    (void)hipFree(s.state);
+    (void)hipFree(s.hist0);
+    (void)hipFree(s.hist1);
+    (void)hipFree(s.glob);
+    (void)hipFree(s.cand);
+    (void)hipFree(s.list2);
+    (void)hipFree(s.tile_sums);
+    for (int i = 0; i < kRing; ++i) {
+        if (ctx->h_ring[i]) (void)hipHostFree(ctx->h_ring[i]);
+        if (ctx->ring_event[i]) (void)hipEventDestroy(ctx->ring_event[i]);
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t pac_keep_count(uint64_t n, double sparsity) {
+    if (!(sparsity >= 0.0 && sparsity <= 1.0)) return 0;
+    const uint64_t kMillion = 1000000u;
+    const uint64_t ppm = (uint64_t)std::llround(sparsity * 1e6);
+    // n < 2^32 on every path that reaches the device; for larger n do the product in 128 bits.
+    const unsigned __int128 num = (unsigned __int128)n * (kMillion - ppm) + (kMillion - 1);
+    return (uint64_t)(num / kMillion);
+}
+
+uint64_t pac_mask_words(uint64_t n) { return n / 64 + (n % 64 != 0 ? 1 : 0); }
+
+const char* pac_last_error(const pac_ctx* ctx) { return ctx ? ctx->err : g_create_error; }
+
+pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_t max_segments) {
+    if (!out) return fail(nullptr, PAC_ERR_ARG, "pac_create: out is NULL");
+    *out = nullptr;
+    if (max_elems == 0 || max_elems >= (1ull << 32))
+        return fail(nullptr, PAC_ERR_RANGE, "pac_create: max_elems must be in [1, 2^32)");
+    if (max_segments == 0 || max_segments > kMaxSegments)
+        return fail(nullptr, PAC_ERR_RANGE, "pac_create: max_segments must be in [1, %u]", kMaxSegments);
+
+    int count = 0;
+    hipError_t e = hipGetDeviceCount(&count);
+    if (e != hipSuccess) return fail(nullptr, PAC_ERR_HIP, "pac_create: hipGetDeviceCount: %s", hipGetErrorString(e));
+    if (hip_device < 0 || hip_device >= count)
+        return fail(nullptr, PAC_ERR_ARG, "pac_create: device %d not in [0, %d)", hip_device, count);
+
+    pac_ctx* ctx = new (std::nothrow) pac_ctx();
+    if (!ctx) return fail(nullptr, PAC_ERR_NOMEM, "pac_create: host allocation failed");
+    ctx->device = hip_device;
+    ctx->max_elems = max_elems;
+    ctx->max_segments = max_segments;
+
+    DeviceGuard guard(hip_device);
+    if (guard.status != hipSuccess) {
+        delete ctx;
+        return fail(nullptr, PAC_ERR_HIP, "pac_create: hipSetDevice: %s", hipGetErrorString(guard.status));
+    }
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, hip_device);
+    if (e != hipSuccess) {
+        delete ctx;
+        return fail(nullptr, PAC_ERR_HIP, "pac_create: hipGetDeviceProperties: %s", hipGetErrorString(e));
+    }
+    ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+    // Candidate lists: one sixteenth of the elements is far above what continuous weight
+    // distributions produce (well under 1 %); tie-heavy scopes beyond it take the in-place path.
+    uint64_t cap = max_elems / 16;
+    if (cap < 65536) cap = 65536;
+    if (cap > max_elems) cap = max_elems;
+    ctx->cand_cap_alloc = (uint32_t)cap;
+
+    pac::MaskScratch& s = ctx->scratch;
+    s.cand_cap = ctx->cand_cap_alloc;
+    const uint64_t words = pac_mask_words(max_elems);
+    const uint64_t scan_tiles = (words + kScanTileWords - 1) / kScanTileWords;
+    const size_t hist0_bytes = (size_t)max_segments * pac::kDigit0Bins * sizeof(uint32_t);
+    const size_t hist1_bytes = (size_t)max_segments * pac::kDigit1Bins * sizeof(uint32_t);
+    bool ok = true;
+    pac_status code = PAC_OK;
+    auto alloc = [&](void** p, size_t bytes) {
+        if (!ok) return;
+        hipError_t r = hipMalloc(p, bytes);
+        if (r != hipSuccess) {
+            ok = false;
+            code = fail(nullptr, PAC_ERR_NOMEM, "pac_create: hipMalloc(%zu): %s", bytes, hipGetErrorString(r));
+        }
+    };
+    alloc((void**)&s.seg, (size_t)max_segments * sizeof(pac::SegDesc));
+    alloc((void**)&s.state, (size_t)max_segments * sizeof(pac::SegState));
+    alloc((void**)&s.hist0, hist0_bytes);
+    alloc((void**)&s.hist1, hist1_bytes);
+    alloc((void**)&s.glob, sizeof(pac::Globals));
+    alloc((void**)&s.cand, (size_t)cap * sizeof(unsigned long long));
+    alloc((void**)&s.list2, (size_t)cap * sizeof(unsigned long long));
+    alloc((void**)&s.tile_sums, (size_t)(scan_tiles + 1) * sizeof(uint32_t));
+    for (int i = 0; ok && i < kRing; ++i) {
+        hipError_t r = hipHostMalloc((void**)&ctx->h_ring[i], (size_t)max_segments * sizeof(pac::SegDesc), hipHostMallocDefault);
+        if (r == hipSuccess) r = hipEventCreateWithFlags(&ctx->ring_event[i], hipEventDisableTiming);
+        if (r != hipSuccess) {
+            ok = false;
+            code = fail(nullptr, PAC_ERR_NOMEM, "pac_create: pinned staging: %s", hipGetErrorString(r));
+        }
+    }
+    if (ok) {
+        // The histograms are all-zero between calls: the kernels that read them clear them.
+        hipError_t r = hipMemset(s.hist0, 0, hist0_bytes);
+        if (r == hipSuccess) r = hipMemset(s.hist1, 0, hist1_bytes);
+        if (r == hipSuccess) r = hipMemset(s.glob, 0, sizeof(pac::Globals));
+        if (r == hipSuccess) r = hipMemset(s.state, 0, (size_t)max_segments * sizeof(pac::SegState));
+        if (r == hipSuccess) r = hipDeviceSynchronize();
+        if (r != hipSuccess) {
+            ok = false;
+            code = fail(nullptr, PAC_ERR_HIP, "pac_create: clearing scratch: %s", hipGetErrorString(r));
+        }
+    }
+    if (!ok) {
+        free_scratch(ctx);
+        delete ctx;
+        return code;
+    }
+    *out = ctx;
+    return PAC_OK;
+}
+
+pac_status pac_destroy(pac_ctx* ctx) {
+    if (!ctx) return PAC_OK;
+    DeviceGuard guard(ctx->device);
+    (void)hipDeviceSynchronize();
+    free_scratch(ctx);
+    delete ctx;
+    return PAC_OK;
+}
+
+pac_status pac_debug_set_candidate_capacity(pac_ctx* ctx, uint64_t capacity) {
+    if (!ctx) return PAC_ERR_ARG;
+    if (capacity > ctx->cand_cap_alloc) capacity = ctx->cand_cap_alloc;
+    ctx->scratch.cand_cap = (uint32_t)capacity;
+    return PAC_OK;
+}
+
+pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n, const uint64_t* h_seg_offsets,
+                          uint32_t nseg, const double* h_sparsity, uint64_t* d_mask, uint32_t* d_prefix,
+                          uint64_t* h_nnz_out, void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    if (!h_seg_offsets || !h_sparsity || nseg == 0)
+        return fail(ctx, PAC_ERR_ARG, "pac_build_mask: segment table missing");
+    if (n >= (1ull << 32) || n > ctx->max_elems)
+        return fail(ctx, PAC_ERR_RANGE, "pac_build_mask: n=%llu exceeds the context capacity %llu",
+                    (unsigned long long)n, (unsigned long long)ctx->max_elems);
+    if (nseg > ctx->max_segments)
+        return fail(ctx, PAC_ERR_RANGE, "pac_build_mask: nseg=%u exceeds the context capacity %u", nseg,
+                    ctx->max_segments);
+    if (h_seg_offsets[0] != 0 || h_seg_offsets[nseg] != n)
+        return fail(ctx, PAC_ERR_ARG, "pac_build_mask: segment offsets must start at 0 and end at n");
+    for (uint32_t s = 0; s < nseg; ++s) {
+        if (h_seg_offsets[s] > h_seg_offsets[s + 1])
+            return fail(ctx, PAC_ERR_ARG, "pac_build_mask: segment offsets not ascending at %u", s);
+        if (!(h_sparsity[s] >= 0.0 && h_sparsity[s] <= 1.0))
+            return fail(ctx, PAC_ERR_RANGE, "pac_build_mask: sparsity[%u] outside [0,1]", s);
+    }
+    if (n > 0) {
+        if (!d_weights || !d_mask || !d_prefix) return fail(ctx, PAC_ERR_ARG, "pac_build_mask: NULL device pointer");
+        if (!is_aligned(d_weights, 4) || !is_aligned(d_mask, 8) || !is_aligned(d_prefix, 4))
+            return fail(ctx, PAC_ERR_ALIGN, "pac_build_mask: weights/prefix need 4-byte, mask 8-byte alignment");
+    }
+
+    // Keep counts: host arithmetic, so the total is known without waiting for the device.
+    std::vector<pac::SegDesc> table(nseg);
+    uint64_t total = 0;
+    for (uint32_t s = 0; s < nseg; ++s) {
+        const uint64_t b = h_seg_offsets[s], e = h_seg_offsets[s + 1];
+        const uint64_t k = pac_keep_count(e - b, h_sparsity[s]);
+        table[s] = pac::SegDesc{(uint32_t)b, (uint32_t)e, (uint32_t)k, 0u};
+        total += k;
+    }
+    if (h_nnz_out) *h_nnz_out = total;
+    if (n == 0) return PAC_OK;
+
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess)
+        return fail(ctx, PAC_ERR_HIP, "pac_build_mask: hipSetDevice: %s", hipGetErrorString(guard.status));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    // Upload the table only when it differs from what the device holds (steady state: never).
+    const bool same = ctx->table_valid && ctx->last_table.size() == table.size() &&
+                      std::memcmp(ctx->last_table.data(), table.data(), table.size() * sizeof(pac::SegDesc)) == 0;
+    if (!same) {
+        const int slot = ctx->ring_next;
+        ctx->ring_next = (slot + 1) % kRing;
+        if (ctx->ring_used[slot]) {
+            hipError_t r = hipEventSynchronize(ctx->ring_event[slot]);   // the copy that last read this slot
+            if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_build_mask: hipEventSynchronize: %s", hipGetErrorString(r));
+        }
+        std::memcpy(ctx->h_ring[slot], table.data(), table.size() * sizeof(pac::SegDesc));
+        hipError_t r = hipMemcpyAsync(ctx->scratch.seg, ctx->h_ring[slot], table.size() * sizeof(pac::SegDesc),
+                                      hipMemcpyHostToDevice, stream);
+        if (r == hipSuccess) r = hipEventRecord(ctx->ring_event[slot], stream);
+        if (r != hipSuccess) {
+            ctx->table_valid = false;
+            return fail(ctx, PAC_ERR_HIP, "pac_build_mask: segment table upload: %s", hipGetErrorString(r));
+        }
+        ctx->ring_used[slot] = true;
+        ctx->last_table.swap(table);
+        ctx->table_valid = true;
+    }
+
+    hipError_t r = pac::launch_build_mask(ctx->scratch, d_weights, (uint32_t)n, nseg,
+                                          reinterpret_cast<unsigned long long*>(d_mask), d_prefix, ctx->num_cu, stream);
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_build_mask: launch: %s", hipGetErrorString(r));
+    return PAC_OK;
+}
+
+static pac_status check_pack_args(pac_ctx* ctx, const char* who, const void* d_dense, const void* d_compact,
+                                  pac_dtype dtype, uint64_t n, uint64_t nnz, const uint64_t* d_mask,
+                                  const uint32_t* d_prefix) {
+    if (dtype != PAC_F32 && dtype != PAC_BF16) return fail(ctx, PAC_ERR_ARG, "%s: unknown dtype %d", who, (int)dtype);
+    if (n >= (1ull << 32)) return fail(ctx, PAC_ERR_RANGE, "%s: n=%llu must be below 2^32", who, (unsigned long long)n);
+    if (nnz > n) return fail(ctx, PAC_ERR_COUNT, "%s: nnz=%llu exceeds n=%llu", who, (unsigned long long)nnz, (unsigned long long)n);
+    if (n == 0) return PAC_OK;
+    if (!d_dense || !d_mask || !d_prefix || (nnz > 0 && !d_compact)) return fail(ctx, PAC_ERR_ARG, "%s: NULL device pointer", who);
+    const uint32_t es = elem_size(dtype);
+    if (!is_aligned(d_dense, es) || !is_aligned(d_compact, es) || !is_aligned(d_mask, 8) || !is_aligned(d_prefix, 4))
+        return fail(ctx, PAC_ERR_ALIGN, "%s: pointer not aligned to its element size", who);
+    return PAC_OK;
+}
+
+pac_status pac_compress(pac_ctx* ctx, const void* d_grad, pac_dtype dtype, uint64_t n, const uint64_t* d_mask,
+                        const uint32_t* d_prefix, void* d_compact, uint64_t nnz, void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    pac_status st = check_pack_args(ctx, "pac_compress", d_grad, d_compact, dtype, n, nnz, d_mask, d_prefix);
+    if (st != PAC_OK || n == 0) return st;
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_compress: hipSetDevice: %s", hipGetErrorString(guard.status));
+    hipError_t r = pac::launch_compress(d_grad, (int)dtype, (uint32_t)n, reinterpret_cast<const unsigned long long*>(d_mask),
+                                        d_prefix, d_compact, (uint32_t)nnz, static_cast<hipStream_t>(hip_stream));
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_compress: launch: %s", hipGetErrorString(r));
+    return PAC_OK;
+}
+
+pac_status pac_decompress(pac_ctx* ctx, const void* d_compact, pac_dtype dtype, uint64_t nnz, const uint64_t* d_mask,
+                          const uint32_t* d_prefix, void* d_dense_out, uint64_t n, void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    pac_status st = check_pack_args(ctx, "pac_decompress", d_dense_out, d_compact, dtype, n, nnz, d_mask, d_prefix);
+    if (st != PAC_OK || n == 0) return st;
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_decompress: hipSetDevice: %s", hipGetErrorString(guard.status));
+    hipError_t r = pac::launch_decompress(d_compact, (int)dtype, (uint32_t)nnz, reinterpret_cast<const unsigned long long*>(d_mask),
+                                          d_prefix, d_dense_out, (uint32_t)n, static_cast<hipStream_t>(hip_stream));
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_decompress: launch: %s", hipGetErrorString(r));
+    return PAC_OK;
+}
+
+pac_status pac_reduce_local(pac_ctx* ctx, const void* const* h_d_compact, uint32_t W, pac_dtype dtype, uint64_t nnz,
+                            void* d_out, void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    if (dtype != PAC_F32 && dtype != PAC_BF16) return fail(ctx, PAC_ERR_ARG, "pac_reduce_local: unknown dtype %d", (int)dtype);
+    if (W < 1 || W > PAC_MAX_WORKERS) return fail(ctx, PAC_ERR_RANGE, "pac_reduce_local: W=%u not in [1, %u]", W, PAC_MAX_WORKERS);
+    if (nnz >= (1ull << 32)) return fail(ctx, PAC_ERR_RANGE, "pac_reduce_local: nnz must be below 2^32");
+    if (!h_d_compact) return fail(ctx, PAC_ERR_ARG, "pac_reduce_local: pointer table is NULL");
+    if (nnz == 0) return PAC_OK;
+    const uint32_t es = elem_size(dtype);
+    pac::WorkerPtrs bufs;
+    for (uint32_t w = 0; w < PAC_MAX_WORKERS; ++w) bufs.p[w] = nullptr;
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!h_d_compact[w]) return fail(ctx, PAC_ERR_ARG, "pac_reduce_local: buffer %u is NULL", w);
+        if (!is_aligned(h_d_compact[w], es)) return fail(ctx, PAC_ERR_ALIGN, "pac_reduce_local: buffer %u misaligned", w);
+        bufs.p[w] = h_d_compact[w];
+    }
+    if (!d_out) return fail(ctx, PAC_ERR_ARG, "pac_reduce_local: d_out is NULL");
+    if (!is_aligned(d_out, es)) return fail(ctx, PAC_ERR_ALIGN, "pac_reduce_local: d_out misaligned");
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_reduce_local: hipSetDevice: %s", hipGetErrorString(guard.status));
+    hipError_t r = pac::launch_reduce(bufs, W, (int)dtype, (uint32_t)nnz, d_out, static_cast<hipStream_t>(hip_stream));
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_reduce_local: launch: %s", hipGetErrorString(r));
+    return PAC_OK;
+}
+
+}  // extern "C"

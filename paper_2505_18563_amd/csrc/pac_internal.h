@@ -1,0 +1,91 @@
+// Internal declarations shared by the translation units of libpactrain (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pac {
+
+// ---- magnitude order ------------------------------------------------------------------------
+// key(w) = bit pattern with the sign cleared (31 bits).  Elements of a prune scope are ordered by
+// the 63-bit composite (key << 32) | (0xFFFFFFFF - flat_index): larger composite = kept first,
+// i.e. |w| descending, flat index ascending.  The selection resolves the composite of the k-th
+// element digit by digit:
+//   digit 0: key bits 30..17 (14 bits, one pass over the weights)
+//   digit 1: key bits 16..5  (12 bits, counted while the candidates of digit 0 are collected)
+//   tail   : key bits 4..0 and the 32 index bits (37 bits, resolved inside one workgroup)
+constexpr uint32_t kDigit0Bits = 14;
+constexpr uint32_t kDigit0Bins = 1u << kDigit0Bits;   // 16384
+constexpr uint32_t kDigit0Shift = 17;                 // within the 31-bit key
+constexpr uint32_t kDigit1Bits = 12;
+constexpr uint32_t kDigit1Bins = 1u << kDigit1Bits;   // 4096
+constexpr uint32_t kDigit1Shift = 5;                  // within the 31-bit key
+constexpr uint32_t kTailBits = 37;                    // composite bits below digit 1
+constexpr uint32_t kNoBin = kDigit0Bins;              // "no element is kept": above every digit
+
+enum SegMode : uint32_t { kModeNone = 0, kModeCand = 1, kModeFull = 2 };
+
+// One prune scope, written by the host.
+struct SegDesc {
+    uint32_t begin;   // first flat element
+    uint32_t end;     // one past the last flat element
+    uint32_t k;       // keep count
+    uint32_t pad;
+};
+
+// Selection state of one prune scope, device only.
+struct SegState {
+    unsigned long long cstar;  // composite of the k-th element: kept iff composite >= cstar
+    uint32_t bin0;             // digit 0 of cstar (kNoBin if k == 0)
+    uint32_t cnt0;             // elements of the scope whose digit 0 equals bin0
+    uint32_t krem0;            // rank of the k-th element among them (1-based, descending)
+    uint32_t mode;             // SegMode
+    uint32_t cand_off;         // first slot of this scope in the candidate list (kModeCand)
+    uint32_t cand_fill;        // slots filled so far
+    uint32_t bin1;             // digit 1 of cstar
+    uint32_t cnt1;             // candidates whose digit 1 equals bin1
+    uint32_t krem1;            // rank of the k-th element among those
+    uint32_t list2_off;        // first slot in the second-level list
+    uint32_t list2_fill;
+    uint32_t pad;
+};
+
+// Counters shared by all scopes of one pac_build_mask call.
+struct Globals {
+    uint32_t cand_total;    // candidate slots handed out
+    uint32_t list2_total;   // second-level slots handed out
+    uint32_t any_full;      // some scope did not fit the candidate list
+    uint32_t pad;
+};
+
+struct MaskScratch {
+    SegDesc* seg;                  // [max_segments]
+    SegState* state;               // [max_segments]
+    uint32_t* hist0;               // [max_segments * kDigit0Bins], all zero between calls
+    uint32_t* hist1;               // [max_segments * kDigit1Bins], all zero between calls
+    Globals* glob;
+    unsigned long long* cand;      // [cand_cap] composites whose digit 0 is the scope's bin0
+    unsigned long long* list2;     // [cand_cap] those whose digit 1 is bin1 as well
+    uint32_t cand_cap;
+    uint32_t* tile_sums;           // per scan tile: set bits, then exclusive offsets
+};
+
+// Launchers (defined in pac_mask.hip / pac_pack.hip).  All enqueue on `stream` and return the
+// first launch error.
+hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
+                             unsigned long long* d_mask, uint32_t* d_prefix, int num_cu, hipStream_t stream);
+
+hipError_t launch_compress(const void* d_grad, int dtype, uint32_t n, const unsigned long long* d_mask,
+                           const uint32_t* d_prefix, void* d_compact, uint32_t nnz, hipStream_t stream);
+
+hipError_t launch_decompress(const void* d_compact, int dtype, uint32_t nnz, const unsigned long long* d_mask,
+                             const uint32_t* d_prefix, void* d_dense, uint32_t n, hipStream_t stream);
+
+struct WorkerPtrs {
+    const void* p[64];
+};
+
+hipError_t launch_reduce(const WorkerPtrs& bufs, uint32_t W, int dtype, uint32_t nnz, void* d_out,
+                         hipStream_t stream);
+
+}  // namespace pac

@@ -1,0 +1,401 @@
+"""GPU parity: every call of the C ABI against the CPU oracle, element by element.
+
+Bar: masks, prefix indices, gathered/scattered values bit-exact; fp32 sums bit-exact (fixed worker
+order); bf16 sums within 1 bf16 ulp on the ordered-integer map of the 16-bit patterns (the kernel
+rounds exactly as the oracle does, so the tests in fact see equality and assert the 1-ulp bar).
+Inputs are seeded and synthetic; the same bytes go to both sides.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pac():
+    import paper_2505_18563_amd as pac_mod
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return pac_mod
+
+
+@pytest.fixture(scope="module")
+def ctx(pac):
+    c = pac.PacContext(max_elems=1 << 25, max_segments=512, device=0)
+    yield c
+    c.close()
+
+
+# ------------------------------------------------------------------------------------ helpers
+def dev(x: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def mask_np(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint64)
+
+
+def prefix_np(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint32)
+
+
+def raw_np(t: torch.Tensor) -> np.ndarray:
+    """Bit patterns of a float32 / bfloat16 tensor as uint32 / uint16."""
+    if t.dtype == torch.float32:
+        return t.cpu().numpy().view(np.uint32)
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def bf16_from_u16(u: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(u.view(np.int16).copy()).cuda().view(torch.bfloat16)
+
+
+def ordered(u16: np.ndarray) -> np.ndarray:
+    """Sign-magnitude 16-bit patterns -> integers ordered like the values."""
+    u = u16.astype(np.int32)
+    return np.where(u & 0x8000, -(u & 0x7FFF), u & 0x7FFF)
+
+
+def check_mask(ctx, w: np.ndarray, offsets, sparsity, label=""):
+    print(f"[build_mask] {label} n={w.size} nseg={len(offsets) - 1}", flush=True)
+    em, ep, ennz = oracle.build_mask(w, offsets, sparsity)
+    wt = dev(w) if w.size else torch.empty(0, dtype=torch.float32, device="cuda")
+    sp = sparsity if not np.isscalar(sparsity) else [float(sparsity)] * (len(offsets) - 1)
+    m, p, nnz = ctx.build_mask(wt, list(map(int, offsets)), list(map(float, sp)))
+    torch.cuda.synchronize()
+    assert nnz == ennz
+    gm, gp = mask_np(m), prefix_np(p)
+    if not np.array_equal(gm, em):
+        bad = np.flatnonzero(gm != em)
+        raise AssertionError(f"{label}: {bad.size} mask words differ, first {bad[:5]}: "
+                             f"gpu {gm[bad[:3]]} oracle {em[bad[:3]]}")
+    assert np.array_equal(gp, ep), f"{label}: prefix differs"
+    return m, p, nnz
+
+
+def weights_of(kind: str, n: int, rng) -> np.ndarray:
+    if kind == "gauss":
+        return (rng.standard_normal(n) * 0.02).astype(np.float32)
+    if kind == "ties":
+        return rng.integers(-6, 7, size=n).astype(np.float32)
+    if kind == "equal":
+        return np.full(n, -1.0, dtype=np.float32)
+    if kind == "zeros_half":
+        w = (rng.standard_normal(n) * 0.02).astype(np.float32)
+        w[rng.random(n) < 0.5] = 0.0
+        return w
+    if kind == "special":
+        pool = np.array([0.0, -0.0, 1e-45, -1e-40, 1.17e-38, 1.0, -1.0, np.inf, -np.inf, np.nan, 65504.0, 3e38],
+                        dtype=np.float32)
+        return rng.choice(pool, size=n)
+    if kind == "narrow":   # all magnitudes inside one digit-0 bin, distinct low bits
+        base = np.float32(0.75).view(np.uint32)
+        return (base + rng.integers(0, 1 << 12, size=n).astype(np.uint32)).view(np.float32)
+    raise ValueError(kind)
+
+
+# ------------------------------------------------------------------------------------ build_mask
+@pytest.mark.parametrize("kind", ["gauss", "ties", "equal", "zeros_half", "special", "narrow"])
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000, 4097, 16384, 16385, 100003, (1 << 20) + 77])
+def test_build_mask_global(ctx, kind, n):
+    rng = np.random.default_rng(sum(map(ord, kind)) * 131 + n)
+    w = weights_of(kind, n, rng)
+    for s in (0.0, 0.5, 0.9, 0.999, 1.0):
+        check_mask(ctx, w, [0, n], s, f"{kind} s={s}")
+
+
+def test_build_mask_segmented_ragged(ctx):
+    rng = np.random.default_rng(21)
+    sizes = [0, 5, 64, 1, 63, 0, 129, 1000, 2, 64, 16384, 7, 40000, 16385, 0, 3, 70001, 0]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(off[-1])
+    for kind in ("gauss", "ties", "equal"):
+        w = weights_of(kind, n, rng)
+        sp = rng.choice([0.0, 0.3, 0.5, 0.9, 0.95, 1.0], size=len(sizes))
+        check_mask(ctx, w, off, sp, f"ragged {kind}")
+
+
+def test_build_mask_many_small_segments(ctx):
+    rng = np.random.default_rng(22)
+    sizes = rng.integers(0, 300, size=400)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    w = weights_of("ties", int(off[-1]), rng)
+    sp = rng.choice([0.1, 0.5, 0.9], size=sizes.size)
+    check_mask(ctx, w, off, sp, "400 small scopes")
+
+
+def test_build_mask_in_place_selection_when_candidates_do_not_fit(pac):
+    """A tiny candidate list forces the scopes with many equal magnitudes onto the in-place path."""
+    rng = np.random.default_rng(23)
+    c = pac.PacContext(max_elems=1 << 21, max_segments=8, device=0)
+    try:
+        pac.pac_debug_set_candidate_capacity(c.handle, 1000)
+        n = 300000
+        for kind in ("equal", "ties", "zeros_half", "gauss"):
+            w = weights_of(kind, n, rng)
+            check_mask(c, w, [0, n], 0.7, f"small-capacity {kind}")
+            check_mask(c, w, [0, 1000, 150000, 150001, n], [0.5, 0.9, 0.0, 0.3], f"small-capacity segmented {kind}")
+    finally:
+        c.close()
+
+
+def test_build_mask_is_deterministic(ctx):
+    rng = np.random.default_rng(24)
+    n = (1 << 21) + 13
+    w = dev(weights_of("ties", n, rng))
+    first = None
+    for _ in range(20):
+        m, p, _ = ctx.build_mask(w, [0, n // 3, n], [0.8, 0.6])
+        torch.cuda.synchronize()
+        got = (mask_np(m).copy(), prefix_np(p).copy())
+        if first is None:
+            first = got
+        assert np.array_equal(got[0], first[0]) and np.array_equal(got[1], first[1])
+
+
+def test_build_mask_unaligned_weights_pointer(ctx):
+    rng = np.random.default_rng(25)
+    n = 70000
+    w = weights_of("gauss", n + 3, rng)
+    big = dev(w)
+    for shift in (1, 2, 3):
+        view = big[shift:shift + n]
+        em, ep, _ = oracle.build_mask(w[shift:shift + n], [0, n], 0.9)
+        m, p, _ = ctx.build_mask(view, [0, n], 0.9)
+        torch.cuda.synchronize()
+        assert np.array_equal(mask_np(m), em) and np.array_equal(prefix_np(p), ep)
+
+
+# ------------------------------------------------------------------------- compress / decompress
+def make_grad(n, dtype, rng):
+    g32 = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    g32[::97] = -0.0
+    if dtype == "f32":
+        g32[5::1013] = np.nan
+        return g32, dev(g32)
+    u16 = oracle.f32_to_bf16(g32)
+    return u16, bf16_from_u16(u16)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n", [1, 7, 64, 1000, 4099, 262144 + 5, (1 << 20) + 123])
+@pytest.mark.parametrize("s", [0.0, 0.5, 0.9, 1.0])
+def test_compress_decompress_match_oracle(ctx, dtype, n, s):
+    rng = np.random.default_rng(n * 7 + int(s * 10))
+    w = weights_of("gauss", n, rng)
+    em, ep, k = oracle.build_mask(w, [0, n], s)
+    m, p = dev(em.view(np.int64)), dev(ep.view(np.int32))
+    code = oracle.F32 if dtype == "f32" else oracle.BF16
+    g_np, g_t = make_grad(n, dtype, rng)
+    print(f"[compress] {dtype} n={n} s={s} k={k}", flush=True)
+    c = ctx.compress(g_t, m, p, k)
+    torch.cuda.synchronize()
+    ec = oracle.compress(g_np, em, k, code)
+    assert np.array_equal(raw_np(c), ec.view(raw_np(c).dtype))
+    d = ctx.decompress(c, m, p, n)
+    torch.cuda.synchronize()
+    ed = oracle.decompress(ec, em, n, code)
+    assert np.array_equal(raw_np(d), ed.view(raw_np(d).dtype))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compress_decompress_unaligned_buffers(ctx, dtype):
+    rng = np.random.default_rng(31)
+    n = 50001
+    w = weights_of("gauss", n, rng)
+    em, ep, k = oracle.build_mask(w, [0, n], 0.8)
+    m, p = dev(em.view(np.int64)), dev(ep.view(np.int32))
+    code = oracle.F32 if dtype == "f32" else oracle.BF16
+    g_np, g_t = make_grad(n + 8, dtype, rng)
+    for shift in (1, 3):
+        gv = g_t[shift:shift + n]
+        ec = oracle.compress(g_np[shift:shift + n], em, k, code)
+        cbuf = torch.zeros(k + 8, dtype=g_t.dtype, device="cuda")
+        cv = cbuf[shift:shift + k]
+        ctx.compress(gv, m, p, k, out=cv)
+        dbuf = torch.full((n + 8,), 7.0, dtype=g_t.dtype, device="cuda")
+        dv = dbuf[shift:shift + n]
+        ctx.decompress(cv, m, p, n, out=dv)
+        torch.cuda.synchronize()
+        assert np.array_equal(raw_np(cv), ec.view(raw_np(cv).dtype))
+        ed = oracle.decompress(ec, em, n, code)
+        assert np.array_equal(raw_np(dv), ed.view(raw_np(dv).dtype))
+        # neighbours of the output views are untouched
+        assert float(dbuf[shift - 1]) == 7.0 and float(dbuf[shift + n]) == 7.0
+        assert float(cbuf[shift - 1]) == 0.0 and float(cbuf[shift + k]) == 0.0
+
+
+# ------------------------------------------------------------------------------------------ sum
+@pytest.mark.parametrize("W", [1, 2, 4, 5, 8, 16, 17, 64])
+@pytest.mark.parametrize("nnz", [1, 9, 1000, 65536 + 3])
+def test_reduce_f32_is_bit_exact_left_fold(ctx, W, nnz):
+    rng = np.random.default_rng(W * 1000 + nnz)
+    bufs = [(rng.standard_normal(nnz) * 10.0 ** rng.integers(-8, 8)).astype(np.float32) for _ in range(W)]
+    bufs[0][::50] = -0.0
+    bufs[-1][3::70] = np.float32(1e-42)        # denormals must survive
+    if W > 1:
+        bufs[1][1::50] = np.inf
+    exp = oracle.reduce_local(bufs, oracle.F32)
+    out = ctx.reduce_local([dev(b) for b in bufs])
+    torch.cuda.synchronize()
+    assert np.array_equal(raw_np(out), exp.view(np.uint32))
+
+
+def test_reduce_f32_keeps_denormal_results(ctx):
+    a = np.full(1000, 1e-41, dtype=np.float32)
+    b = np.full(1000, 2e-41, dtype=np.float32)
+    exp = oracle.reduce_local([a, b], oracle.F32)
+    assert np.all(exp > 0)
+    out = ctx.reduce_local([dev(a), dev(b)])
+    torch.cuda.synchronize()
+    assert np.array_equal(raw_np(out), exp.view(np.uint32))
+
+
+@pytest.mark.parametrize("W", [1, 3, 8, 16, 33])
+@pytest.mark.parametrize("nnz", [1, 15, 4096 + 7, 300001])
+def test_reduce_bf16_within_one_ulp(ctx, W, nnz):
+    rng = np.random.default_rng(W * 77 + nnz)
+    bufs = [oracle.f32_to_bf16((rng.standard_normal(nnz) * 1e-4).astype(np.float32)) for _ in range(W)]
+    bufs[0][::41] = 0x8000                       # -0.0
+    bufs[W // 2][7::91] = 0x7FC0                 # NaN
+    exp = oracle.reduce_local(bufs, oracle.BF16)
+    out = ctx.reduce_local([bf16_from_u16(b) for b in bufs])
+    torch.cuda.synchronize()
+    got = raw_np(out)
+    nan = (exp & 0x7FFF) > 0x7F80
+    assert np.array_equal((got & 0x7FFF) > 0x7F80, nan)
+    assert np.max(np.abs(ordered(got[~nan]) - ordered(exp[~nan])), initial=0) <= 1
+    # the kernel implements the same rounding, so in fact the patterns agree
+    assert np.array_equal(got[~nan], exp[~nan])
+
+
+def test_reduce_unaligned_and_in_place(ctx):
+    rng = np.random.default_rng(33)
+    nnz = 10007
+    bufs = [(rng.standard_normal(nnz + 4)).astype(np.float32) for _ in range(4)]
+    dbufs = [dev(b) for b in bufs]
+    views = [d[1:1 + nnz] for d in dbufs]
+    exp = oracle.reduce_local([b[1:1 + nnz] for b in bufs], oracle.F32)
+    ctx.reduce_local(views, out=views[2])        # output aliases input 2
+    torch.cuda.synchronize()
+    assert np.array_equal(raw_np(views[2]), exp.view(np.uint32))
+
+
+# ------------------------------------------------------------------------------- whole path
+def run_pipeline(ctx, wl, step=0):
+    sparsity = wl.sparsity_at(step)
+    w_np = wl.weights.numpy()
+    em, ep, k = oracle.build_mask(w_np, wl.scope_offsets, sparsity)
+    code = oracle.F32 if wl.dtype == "f32" else oracle.BF16
+    g_np = [raw_np(g) for g in wl.grads]
+    e_compact = [oracle.compress(g.view(np.float32) if code == oracle.F32 else g, em, k, code) for g in g_np]
+    e_red = oracle.reduce_local(e_compact, code)
+    e_out = oracle.decompress(e_red, em, wl.n, code)
+
+    print(f"[pipeline] {wl.name} n={wl.n} W={wl.workers} dtype={wl.dtype} s={sparsity[0]}", flush=True)
+    wt = wl.weights.cuda()
+    m, p, nnz = ctx.build_mask(wt, wl.scope_offsets, sparsity)
+    assert nnz == k
+    compact = [ctx.compress(g.cuda(), m, p, nnz) for g in wl.grads]
+    red = ctx.reduce_local(compact, nnz)
+    out = ctx.decompress(red, m, p, wl.n, nnz)
+    torch.cuda.synchronize()
+    assert np.array_equal(mask_np(m), em)
+    assert np.array_equal(prefix_np(p), ep)
+    for c, ec in zip(compact, e_compact):
+        assert np.array_equal(raw_np(c), ec.view(raw_np(c).dtype))
+    if code == oracle.F32:
+        assert np.array_equal(raw_np(red), e_red.view(np.uint32))
+        assert np.array_equal(raw_np(out), e_out.view(np.uint32))
+    else:
+        gr, go = raw_np(red), raw_np(out)
+        assert np.max(np.abs(ordered(gr) - ordered(e_red)), initial=0) <= 1
+        assert np.max(np.abs(ordered(go) - ordered(e_out)), initial=0) <= 1
+        assert np.array_equal(gr, e_red) and np.array_equal(go, e_out)
+        # pruned positions are exactly +0 whatever the tolerance on kept ones
+        kept = np.unpackbits(em.view(np.uint8), bitorder="little")[:wl.n].astype(bool)
+        assert not go[~kept].any()
+
+
+def test_pipeline_config1_single_tensor(ctx):
+    run_pipeline(ctx, make_workload(1))
+
+
+def test_pipeline_config2_resnet18_per_layer(ctx):
+    run_pipeline(ctx, make_workload(2))
+
+
+def test_pipeline_config3_reduced_bert_like_student_t(ctx):
+    run_pipeline(ctx, make_workload(3, reduced=True))
+
+
+def test_pipeline_config4_reduced_bf16_payload(ctx):
+    run_pipeline(ctx, make_workload(4, reduced=True))
+
+
+@pytest.mark.parametrize("step", [0, 1, 2])
+def test_pipeline_config5_reduced_sparsity_schedule(ctx, step):
+    run_pipeline(ctx, make_workload(5, reduced=True), step)
+
+
+# ------------------------------------------------------------------------------ error paths
+def test_argument_errors_are_status_codes_not_faults(pac, ctx):
+    n = 1000
+    w = torch.zeros(n, device="cuda")
+    m = torch.zeros(16, dtype=torch.int64, device="cuda")
+    p = torch.zeros(16, dtype=torch.int32, device="cuda")
+    h = ctx.handle
+    with pytest.raises(pac.PacError) as e:
+        pac.pac_build_mask(h, w, [0, n], [1.5], m, p)
+    assert e.value.status == -3
+    with pytest.raises(pac.PacError) as e:
+        pac.pac_build_mask(h, w, [0, 600, 500, n], [0.5, 0.5, 0.5], m, p)
+    assert e.value.status == -1
+    with pytest.raises(pac.PacError) as e:
+        pac.pac_build_mask(h, w, [0, n - 1], [0.5], m, p)
+    assert e.value.status == -1
+    big = torch.zeros(8, device="cuda")
+    with pytest.raises(pac.PacError) as e:       # nnz larger than n
+        pac.binding._check(h, pac.load_library().pac_compress(h, big.data_ptr(), 0, 8, m.data_ptr(), p.data_ptr(),
+                                                              big.data_ptr(), 9, 0))
+    assert e.value.status == -4
+    with pytest.raises(pac.PacError) as e:       # odd address for a 4-byte type
+        pac.binding._check(h, pac.load_library().pac_compress(h, big.data_ptr() + 2, 0, 4, m.data_ptr(), p.data_ptr(),
+                                                              big.data_ptr(), 1, 0))
+    assert e.value.status == -2
+    with pytest.raises(pac.PacError) as e:
+        pac.pac_reduce_local(h, [], big, 4)
+    assert e.value.status == -3
+    with pytest.raises(pac.PacError) as e:       # beyond the context's capacity
+        pac.pac_build_mask(h, torch.zeros((1 << 25) + 64, device="cuda"), [0, (1 << 25) + 64], [0.5],
+                           torch.zeros((1 << 19) + 1, dtype=torch.int64, device="cuda"),
+                           torch.zeros((1 << 19) + 1, dtype=torch.int32, device="cuda"))
+    assert e.value.status == -3
+
+
+def test_inconsistent_nnz_never_writes_out_of_bounds(ctx):
+    """A caller passing a smaller nnz than the mask holds gets a truncated result, never a fault."""
+    rng = np.random.default_rng(41)
+    n = 20000
+    w = weights_of("gauss", n, rng)
+    em, ep, k = oracle.build_mask(w, [0, n], 0.5)
+    m, p = dev(em.view(np.int64)), dev(ep.view(np.int32))
+    g = dev(np.ones(n, np.float32))
+    buf = torch.zeros(k, dtype=torch.float32, device="cuda")
+    ctx.compress(g, m, p, k // 2, out=buf)
+    torch.cuda.synchronize()
+    assert float(buf[k // 2:].abs().sum()) == 0.0
+
+
+def test_empty_input_is_accepted(pac, ctx):
+    e = torch.empty(0, device="cuda")
+    m = torch.empty(0, dtype=torch.int64, device="cuda")
+    p = torch.empty(0, dtype=torch.int32, device="cuda")
+    assert pac.pac_build_mask(ctx.handle, e, [0, 0], [0.5], m, p) == 0
+    pac.pac_compress(ctx.handle, e, m, p, e, 0)
+    pac.pac_decompress(ctx.handle, e, m, p, e, 0)
+    pac.pac_reduce_local(ctx.handle, [e], e, 0)
+    torch.cuda.synchronize()
