@@ -3,8 +3,9 @@
 // All three are streaming kernels bound by HBM bandwidth.  A lane owns one 16-byte chunk of the
 // dense tensor (8 bf16 or 4 fp32 elements); consecutive lanes own consecutive chunks, so dense
 // loads and stores are full 128-bit coalesced accesses.  The mask word and its prefix entry of the
-// chunk are fetched by every lane that shares them (one cache line per wave).  Compact accesses of
-// a wave fall into one short contiguous range.
+// chunk are fetched by every lane that shares them (one cache line per wave).  The compact side of
+// a wave is one short contiguous range; it goes through the wave's LDS staging area so that it,
+// too, moves in 128-bit accesses instead of one narrow access per surviving element.
 #include "pac_internal.h"
 
 namespace pac {
@@ -43,60 +44,126 @@ __device__ __forceinline__ uint16_t elem_of<uint16_t>(const uint4& v, int e) {
     return (uint16_t)((e & 1) ? (d >> 16) : d);
 }
 
-// ------------------------------------------------------------------------------------ compress
-template <typename T, int UNROLL>
-__global__ __launch_bounds__(kBlock) void compress_vec_kernel(const uint4* __restrict__ grad, uint32_t n,
-                                                              const unsigned long long* __restrict__ mask,
-                                                              const uint32_t* __restrict__ prefix,
-                                                              T* __restrict__ compact, uint32_t nnz) {
-    constexpr uint32_t E = Chunk<T>::kElems;
-    const uint32_t n_chunks = n / E;
-    const uint32_t first = blockIdx.x * (uint32_t)(kBlock * UNROLL) + threadIdx.x;
+// ------------------------------------------------------------------------- tile geometry
+// One wave owns a tile of U*64 chunks = U*E mask words.  Because a tile starts on a mask-word
+// boundary, its first compact slot S0 and the slot after its last survivor S1 are two entries of the
+// prefix array (S1 = nnz for the tile that holds the end of the tensor): wave-uniform values, read
+// with scalar loads, no cross-lane reduction.  Survivors are staged in the wave's LDS region at
+// (slot - S0 + phase), where phase makes LDS 16-byte chunks line up with 16-byte chunks of the
+// compact buffer; the compact range is then moved with at most one head, one tail (element-wise)
+// and ceil(T/64E) full 16-byte accesses per lane.  No workgroup barrier is involved.
+constexpr int kPackBlock = 128;
+constexpr int kPackWaves = kPackBlock / 64;
+constexpr int kPackU = 2;
 
-    uint4 v[UNROLL];
-    unsigned long long word[UNROLL];
-    uint32_t pre[UNROLL];
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <typename T, int U>
+struct Tile {
+    static constexpr uint32_t E = 16 / sizeof(T);
+    static constexpr uint32_t kChunks = 64 * U;
+    static constexpr uint32_t kElems = kChunks * E;
+    static constexpr uint32_t kWords = kElems / 64;       // = U * E
+    static constexpr uint32_t kStage = kElems + 2 * E;    // + phase + tail elements
+};
+
+__device__ __forceinline__ void wave_lds_sync() {
+    // Orders this wave's LDS writes before its later LDS reads of other lanes' data.
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <typename T>
+__device__ __forceinline__ uint32_t phase_of(const T* p) {
+    return (uint32_t)((reinterpret_cast<uintptr_t>(p) / sizeof(T)) & (16 / sizeof(T) - 1));
+}
+
+// ------------------------------------------------------------------------------------ compress
+template <typename T, int U>
+__global__ __launch_bounds__(kPackBlock) void compress_tile_kernel(const u32x4* __restrict__ grad, uint32_t n,
+                                                                   const unsigned long long* __restrict__ mask,
+                                                                   const uint32_t* __restrict__ prefix,
+                                                                   T* __restrict__ compact, uint32_t nnz) {
+    typedef Tile<T, U> G;
+    constexpr uint32_t E = G::E;
+    __shared__ __attribute__((aligned(16))) T stage[kPackWaves][G::kStage];
+
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t tile = blockIdx.x * kPackWaves + wave;
+    if ((unsigned long long)tile * G::kElems >= n) return;
+    const uint32_t n_chunks = n / E;
+    const uint32_t words = (uint32_t)(((unsigned long long)n + 63) >> 6);
+    const uint32_t chunk0 = tile * G::kChunks;
+
+    u32x4 v[U];
+    unsigned long long word[U];
+    uint32_t pre[U];
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-        const uint32_t q = first + (uint32_t)u * kBlock;
+    for (int u = 0; u < U; ++u) {
+        const uint32_t q = chunk0 + (uint32_t)u * 64 + lane;
         word[u] = 0;
         pre[u] = 0;
-        v[u] = make_uint4(0, 0, 0, 0);
+        v[u] = (u32x4){0, 0, 0, 0};
         if (q < n_chunks) {
-            v[u] = grad[q];
+            v[u] = __builtin_nontemporal_load(grad + q);
             const uint32_t w = (q * E) >> 6;
             word[u] = mask[w];
             pre[u] = prefix[w];
         }
     }
+
+    const uint32_t w0 = tile * G::kWords;
+    const uint32_t w1 = w0 + G::kWords;
+    const uint32_t s0 = prefix[w0];
+    const uint32_t s1 = w1 < words ? prefix[w1] : nnz;
+    // A mask/prefix/nnz triple that does not fit together must not make the kernel write out of bounds.
+    if (s0 > s1 || s1 > nnz || s1 - s0 > G::kElems) return;
+    const uint32_t count = s1 - s0;
+    const uint32_t ph = phase_of(compact + s0);
+    T* my = stage[wave];
+
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-        const uint32_t q = first + (uint32_t)u * kBlock;
-        uint32_t sub, slot;
-        chunk_meta<T>(q, word[u], pre[u], sub, slot);
-        // A mask/prefix pair that disagrees with nnz must not make the kernel write out of bounds.
-        if (slot > nnz || (uint32_t)__popc(sub) > nnz - slot) sub = 0;
-        T* out = compact + slot;
+    for (int u = 0; u < U; ++u) {
+        const uint32_t q = chunk0 + (uint32_t)u * 64 + lane;
+        const uint32_t bitoff = (q * E) & 63u;
+        uint32_t sub = (uint32_t)(word[u] >> bitoff) & ((1u << E) - 1u);
+        const uint32_t pos = pre[u] + popc64(word[u] & ((1ull << bitoff) - 1ull)) - s0 + ph;
+        if (pos > G::kStage - E) sub = 0;
+        T* p = my + pos;
+        const uint4 vv = make_uint4(v[u].x, v[u].y, v[u].z, v[u].w);
 #pragma unroll
         for (int e = 0; e < (int)E; ++e) {
             if (sub & (1u << e)) {
-                *out = elem_of<T>(v[u], e);
-                ++out;
+                *p = elem_of<T>(vv, e);
+                ++p;
             }
         }
     }
-
-    // Elements after the last whole chunk (n not a multiple of the chunk size).
-    if (blockIdx.x == gridDim.x - 1) {
-        const uint32_t i = n_chunks * E + threadIdx.x;
-        if (threadIdx.x < E && i < n) {
+    // Elements after the last whole chunk (n not a multiple of E) belong to the tile they follow.
+    if (tile == n_chunks / G::kChunks) {
+        const uint32_t i = n_chunks * E + lane;
+        if (lane < E && i < n) {
             const unsigned long long wd = mask[i >> 6];
             if ((wd >> (i & 63u)) & 1ull) {
-                const uint32_t slot = prefix[i >> 6] + popc64(wd & ((1ull << (i & 63u)) - 1ull));
-                if (slot < nnz) compact[slot] = reinterpret_cast<const T*>(grad)[i];
+                const uint32_t pos = prefix[i >> 6] + popc64(wd & ((1ull << (i & 63u)) - 1ull)) - s0 + ph;
+                if (pos < G::kStage) my[pos] = reinterpret_cast<const T*>(grad)[i];
             }
         }
     }
+    wave_lds_sync();
+
+    // LDS [ph, ph + count) -> compact [s0, s1); (compact + s0 - ph) is 16-byte aligned.
+    T* gbase = compact + s0 - ph;
+    const uint32_t a = ph, b = ph + count;
+    uint32_t h_end = (a + E - 1u) & ~(E - 1u);
+    if (h_end > b) h_end = b;
+    if (lane < h_end - a) gbase[a + lane] = my[a + lane];
+    for (uint32_t c = h_end / E + lane; c < b / E; c += 64)
+        *reinterpret_cast<u32x4*>(gbase + c * E) = *reinterpret_cast<const u32x4*>(my + c * E);
+    uint32_t t0 = b & ~(E - 1u);
+    if (t0 < h_end) t0 = h_end;
+    if (lane < b - t0) gbase[t0 + lane] = my[t0 + lane];
 }
 
 // Any element alignment: one element per lane, lane b of a wave owns bit b of one mask word.
@@ -117,43 +184,51 @@ __global__ __launch_bounds__(kBlock) void compress_scalar_kernel(const T* __rest
 
 // ---------------------------------------------------------------------------------- decompress
 template <typename T>
-__device__ __forceinline__ uint4 gather_chunk(const T* __restrict__ src, uint32_t sub);
+__device__ __forceinline__ u32x4 gather_chunk(const T* p, uint32_t sub);
 template <>
-__device__ __forceinline__ uint4 gather_chunk<uint32_t>(const uint32_t* __restrict__ src, uint32_t sub) {
-    uint4 o = make_uint4(0, 0, 0, 0);
-    if (sub & 1u) { o.x = *src; ++src; }
-    if (sub & 2u) { o.y = *src; ++src; }
-    if (sub & 4u) { o.z = *src; ++src; }
-    if (sub & 8u) { o.w = *src; }
+__device__ __forceinline__ u32x4 gather_chunk<uint32_t>(const uint32_t* p, uint32_t sub) {
+    u32x4 o = (u32x4){0, 0, 0, 0};
+    if (sub & 1u) { o.x = *p; ++p; }
+    if (sub & 2u) { o.y = *p; ++p; }
+    if (sub & 4u) { o.z = *p; ++p; }
+    if (sub & 8u) { o.w = *p; }
     return o;
 }
 template <>
-__device__ __forceinline__ uint4 gather_chunk<uint16_t>(const uint16_t* __restrict__ src, uint32_t sub) {
+__device__ __forceinline__ u32x4 gather_chunk<uint16_t>(const uint16_t* p, uint32_t sub) {
     uint32_t d[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         if (sub & (1u << e)) {
-            d[e >> 1] |= (uint32_t)(*src) << ((e & 1) * 16);
-            ++src;
+            d[e >> 1] |= (uint32_t)(*p) << ((e & 1) * 16);
+            ++p;
         }
     }
-    return make_uint4(d[0], d[1], d[2], d[3]);
+    return (u32x4){d[0], d[1], d[2], d[3]};
 }
 
-template <typename T, int UNROLL>
-__global__ __launch_bounds__(kBlock) void decompress_vec_kernel(const T* __restrict__ compact, uint32_t nnz,
-                                                                const unsigned long long* __restrict__ mask,
-                                                                const uint32_t* __restrict__ prefix,
-                                                                uint4* __restrict__ dense, uint32_t n) {
-    constexpr uint32_t E = Chunk<T>::kElems;
-    const uint32_t n_chunks = n / E;
-    const uint32_t first = blockIdx.x * (uint32_t)(kBlock * UNROLL) + threadIdx.x;
+template <typename T, int U>
+__global__ __launch_bounds__(kPackBlock) void decompress_tile_kernel(const T* __restrict__ compact, uint32_t nnz,
+                                                                     const unsigned long long* __restrict__ mask,
+                                                                     const uint32_t* __restrict__ prefix,
+                                                                     u32x4* __restrict__ dense, uint32_t n) {
+    typedef Tile<T, U> G;
+    constexpr uint32_t E = G::E;
+    __shared__ __attribute__((aligned(16))) T stage[kPackWaves][G::kStage];
 
-    unsigned long long word[UNROLL];
-    uint32_t pre[UNROLL];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t tile = blockIdx.x * kPackWaves + wave;
+    if ((unsigned long long)tile * G::kElems >= n) return;
+    const uint32_t n_chunks = n / E;
+    const uint32_t words = (uint32_t)(((unsigned long long)n + 63) >> 6);
+    const uint32_t chunk0 = tile * G::kChunks;
+
+    unsigned long long word[U];
+    uint32_t pre[U];
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-        const uint32_t q = first + (uint32_t)u * kBlock;
+    for (int u = 0; u < U; ++u) {
+        const uint32_t q = chunk0 + (uint32_t)u * 64 + lane;
         word[u] = 0;
         pre[u] = 0;
         if (q < n_chunks) {
@@ -162,25 +237,51 @@ __global__ __launch_bounds__(kBlock) void decompress_vec_kernel(const T* __restr
             pre[u] = prefix[w];
         }
     }
+
+    const uint32_t w0 = tile * G::kWords;
+    const uint32_t w1 = w0 + G::kWords;
+    const uint32_t s0 = prefix[w0];
+    const uint32_t s1 = w1 < words ? prefix[w1] : nnz;
+    // Inconsistent metadata: read nothing, the tile's outputs become zero.
+    const bool sane = s0 <= s1 && s1 <= nnz && s1 - s0 <= G::kElems;
+    const uint32_t count = sane ? s1 - s0 : 0u;
+    const uint32_t ph = phase_of(compact + s0);
+    T* my = stage[wave];
+
+    // compact [s0, s1) -> LDS [ph, ph + count)
+    if (count != 0) {
+        const T* gbase = compact + s0 - ph;
+        const uint32_t a = ph, b = ph + count;
+        uint32_t h_end = (a + E - 1u) & ~(E - 1u);
+        if (h_end > b) h_end = b;
+        if (lane < h_end - a) my[a + lane] = gbase[a + lane];
+        for (uint32_t c = h_end / E + lane; c < b / E; c += 64)
+            *reinterpret_cast<u32x4*>(my + c * E) = *reinterpret_cast<const u32x4*>(gbase + c * E);
+        uint32_t t0 = b & ~(E - 1u);
+        if (t0 < h_end) t0 = h_end;
+        if (lane < b - t0) my[t0 + lane] = gbase[t0 + lane];
+    }
+    wave_lds_sync();
+
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-        const uint32_t q = first + (uint32_t)u * kBlock;
+    for (int u = 0; u < U; ++u) {
+        const uint32_t q = chunk0 + (uint32_t)u * 64 + lane;
         if (q < n_chunks) {
-            uint32_t sub, slot;
-            chunk_meta<T>(q, word[u], pre[u], sub, slot);
-            if (slot > nnz || (uint32_t)__popc(sub) > nnz - slot) sub = 0;   // never read beyond the compact buffer
-            dense[q] = gather_chunk<T>(compact + slot, sub);
+            const uint32_t bitoff = (q * E) & 63u;
+            uint32_t sub = (uint32_t)(word[u] >> bitoff) & ((1u << E) - 1u);
+            const uint32_t pos = pre[u] + popc64(word[u] & ((1ull << bitoff) - 1ull)) - s0 + ph;
+            if (!sane || pos > ph + count || (uint32_t)__popc(sub) > ph + count - pos) sub = 0;
+            __builtin_nontemporal_store(gather_chunk<T>(my + pos, sub), dense + q);
         }
     }
-
-    if (blockIdx.x == gridDim.x - 1) {
-        const uint32_t i = n_chunks * E + threadIdx.x;
-        if (threadIdx.x < E && i < n) {
+    if (tile == n_chunks / G::kChunks) {
+        const uint32_t i = n_chunks * E + lane;
+        if (lane < E && i < n) {
             const unsigned long long wd = mask[i >> 6];
             T val = 0;
             if ((wd >> (i & 63u)) & 1ull) {
-                const uint32_t slot = prefix[i >> 6] + popc64(wd & ((1ull << (i & 63u)) - 1ull));
-                if (slot < nnz) val = compact[slot];
+                const uint32_t pos = prefix[i >> 6] + popc64(wd & ((1ull << (i & 63u)) - 1ull)) - s0 + ph;
+                if (sane && pos < ph + count) val = my[pos];
             }
             reinterpret_cast<T*>(dense)[i] = val;
         }
@@ -269,6 +370,11 @@ __device__ __forceinline__ void store_scalar(void* p, uint32_t j, float f) {
     else static_cast<uint16_t*>(p)[j] = (uint16_t)f32_to_bf16_bits(f);
 }
 
+__device__ __forceinline__ uint4 load_stream(const void* base, uint32_t q) {
+    const u32x4 v = __builtin_nontemporal_load(static_cast<const u32x4*>(base) + q);   // read once, never reused
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 template <int DT>
 __global__ __launch_bounds__(kBlock) void reduce_vec_kernel(WorkerPtrs bufs, uint32_t W, uint32_t nnz, void* out) {
     constexpr uint32_t E = DT == 0 ? 4 : 8;
@@ -276,17 +382,18 @@ __global__ __launch_bounds__(kBlock) void reduce_vec_kernel(WorkerPtrs bufs, uin
     const uint32_t q = blockIdx.x * (uint32_t)kBlock + threadIdx.x;
     if (q < n_chunks) {
         Acc<DT> acc;
-        acc.set(static_cast<const uint4*>(bufs.p[0])[q]);
+        acc.set(load_stream(bufs.p[0], q));
         uint32_t w = 1;
         for (; w + 4 <= W; w += 4) {   // four loads in flight, adds in worker order
-            const uint4 v0 = static_cast<const uint4*>(bufs.p[w])[q];
-            const uint4 v1 = static_cast<const uint4*>(bufs.p[w + 1])[q];
-            const uint4 v2 = static_cast<const uint4*>(bufs.p[w + 2])[q];
-            const uint4 v3 = static_cast<const uint4*>(bufs.p[w + 3])[q];
+            const uint4 v0 = load_stream(bufs.p[w], q);
+            const uint4 v1 = load_stream(bufs.p[w + 1], q);
+            const uint4 v2 = load_stream(bufs.p[w + 2], q);
+            const uint4 v3 = load_stream(bufs.p[w + 3], q);
             acc.add(v0); acc.add(v1); acc.add(v2); acc.add(v3);
         }
-        for (; w < W; ++w) acc.add(static_cast<const uint4*>(bufs.p[w])[q]);
-        static_cast<uint4*>(out)[q] = acc.get();
+        for (; w < W; ++w) acc.add(load_stream(bufs.p[w], q));
+        const uint4 r = acc.get();
+        static_cast<uint4*>(out)[q] = r;
     }
     if (blockIdx.x == gridDim.x - 1) {
         const uint32_t j = n_chunks * E + threadIdx.x;
@@ -316,17 +423,16 @@ inline uint32_t div_up(unsigned long long a, unsigned long long b) { return (uin
 hipError_t launch_compress(const void* d_grad, int dtype, uint32_t n, const unsigned long long* d_mask,
                            const uint32_t* d_prefix, void* d_compact, uint32_t nnz, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    constexpr int U = 4;
     if (aligned16(d_grad)) {
         if (dtype == 0) {
-            const uint32_t blocks = div_up((unsigned long long)n / 4 + 1, kBlock * U);
-            hipLaunchKernelGGL((compress_vec_kernel<uint32_t, U>), dim3(blocks), dim3(kBlock), 0, stream,
-                               static_cast<const uint4*>(d_grad), n, d_mask, d_prefix,
+            const uint32_t tiles = div_up(n, Tile<uint32_t, kPackU>::kElems);
+            hipLaunchKernelGGL((compress_tile_kernel<uint32_t, kPackU>), dim3(div_up(tiles, kPackWaves)),
+                               dim3(kPackBlock), 0, stream, static_cast<const u32x4*>(d_grad), n, d_mask, d_prefix,
                                static_cast<uint32_t*>(d_compact), nnz);
         } else {
-            const uint32_t blocks = div_up((unsigned long long)n / 8 + 1, kBlock * U);
-            hipLaunchKernelGGL((compress_vec_kernel<uint16_t, U>), dim3(blocks), dim3(kBlock), 0, stream,
-                               static_cast<const uint4*>(d_grad), n, d_mask, d_prefix,
+            const uint32_t tiles = div_up(n, Tile<uint16_t, kPackU>::kElems);
+            hipLaunchKernelGGL((compress_tile_kernel<uint16_t, kPackU>), dim3(div_up(tiles, kPackWaves)),
+                               dim3(kPackBlock), 0, stream, static_cast<const u32x4*>(d_grad), n, d_mask, d_prefix,
                                static_cast<uint16_t*>(d_compact), nnz);
         }
     } else {
@@ -346,18 +452,17 @@ hipError_t launch_compress(const void* d_grad, int dtype, uint32_t n, const unsi
 hipError_t launch_decompress(const void* d_compact, int dtype, uint32_t nnz, const unsigned long long* d_mask,
                              const uint32_t* d_prefix, void* d_dense, uint32_t n, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    constexpr int U = 4;
     if (aligned16(d_dense)) {
         if (dtype == 0) {
-            const uint32_t blocks = div_up((unsigned long long)n / 4 + 1, kBlock * U);
-            hipLaunchKernelGGL((decompress_vec_kernel<uint32_t, U>), dim3(blocks), dim3(kBlock), 0, stream,
-                               static_cast<const uint32_t*>(d_compact), nnz, d_mask, d_prefix,
-                               static_cast<uint4*>(d_dense), n);
+            const uint32_t tiles = div_up(n, Tile<uint32_t, kPackU>::kElems);
+            hipLaunchKernelGGL((decompress_tile_kernel<uint32_t, kPackU>), dim3(div_up(tiles, kPackWaves)),
+                               dim3(kPackBlock), 0, stream, static_cast<const uint32_t*>(d_compact), nnz, d_mask,
+                               d_prefix, static_cast<u32x4*>(d_dense), n);
         } else {
-            const uint32_t blocks = div_up((unsigned long long)n / 8 + 1, kBlock * U);
-            hipLaunchKernelGGL((decompress_vec_kernel<uint16_t, U>), dim3(blocks), dim3(kBlock), 0, stream,
-                               static_cast<const uint16_t*>(d_compact), nnz, d_mask, d_prefix,
-                               static_cast<uint4*>(d_dense), n);
+            const uint32_t tiles = div_up(n, Tile<uint16_t, kPackU>::kElems);
+            hipLaunchKernelGGL((decompress_tile_kernel<uint16_t, kPackU>), dim3(div_up(tiles, kPackWaves)),
+                               dim3(kPackBlock), 0, stream, static_cast<const uint16_t*>(d_compact), nnz, d_mask,
+                               d_prefix, static_cast<u32x4*>(d_dense), n);
         }
     } else {
         const uint32_t blocks = div_up(n, kBlock);
