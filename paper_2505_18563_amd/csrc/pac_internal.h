@@ -12,18 +12,16 @@ namespace pac {
 // i.e. |w| descending, flat index ascending.  The selection resolves the composite of the k-th
 // element digit by digit:
 //   digit 0: key bits 30..17 (14 bits, one pass over the weights)
-//   digit 1: key bits 16..5  (12 bits, counted while the candidates of digit 0 are collected)
-//   tail   : key bits 4..0 and the 32 index bits (37 bits, resolved inside one workgroup)
+//   digit 1: key bits 16..6  (11 bits, counted while the candidates of digit 0 are collected)
+//   tail   : key bits 5..0 and the 32 index bits (38 bits, resolved inside one workgroup)
 constexpr uint32_t kDigit0Bits = 14;
 constexpr uint32_t kDigit0Bins = 1u << kDigit0Bits;   // 16384
 constexpr uint32_t kDigit0Shift = 17;                 // within the 31-bit key
-constexpr uint32_t kDigit1Bits = 12;
-constexpr uint32_t kDigit1Bins = 1u << kDigit1Bits;   // 4096
-constexpr uint32_t kDigit1Shift = 5;                  // within the 31-bit key
-constexpr uint32_t kTailBits = 37;                    // composite bits below digit 1
+constexpr uint32_t kDigit1Bits = 11;
+constexpr uint32_t kDigit1Bins = 1u << kDigit1Bits;   // 2048
+constexpr uint32_t kDigit1Shift = kDigit0Shift - kDigit1Bits;   // 6, within the 31-bit key
+constexpr uint32_t kTailBits = 32 + kDigit1Shift;     // composite bits below digit 1
 constexpr uint32_t kNoBin = kDigit0Bins;              // "no element is kept": above every digit
-
-enum SegMode : uint32_t { kModeNone = 0, kModeCand = 1, kModeFull = 2 };
 
 // One prune scope, written by the host.
 struct SegDesc {
@@ -36,26 +34,31 @@ struct SegDesc {
 // Selection state of one prune scope, device only.
 struct SegState {
     unsigned long long cstar;  // composite of the k-th element: kept iff composite >= cstar
+    uint32_t active;           // 0 if k == 0 (nothing kept, nothing to resolve)
     uint32_t bin0;             // digit 0 of cstar (kNoBin if k == 0)
     uint32_t cnt0;             // elements of the scope whose digit 0 equals bin0
     uint32_t krem0;            // rank of the k-th element among them (1-based, descending)
-    uint32_t mode;             // SegMode
-    uint32_t cand_off;         // first slot of this scope in the candidate list (kModeCand)
-    uint32_t cand_fill;        // slots filled so far
     uint32_t bin1;             // digit 1 of cstar
     uint32_t cnt1;             // candidates whose digit 1 equals bin1
     uint32_t krem1;            // rank of the k-th element among those
-    uint32_t list2_off;        // first slot in the second-level list
-    uint32_t list2_fill;
+    uint32_t list2_off;        // first slot of this scope in the second-level list
+    uint32_t list2_fill;       // slots filled so far
     uint32_t pad;
 };
 
+// The candidate list is split into regions with one fill counter each: an atomic on one address
+// costs about 10 ns and is serialised, so the appends of a call are spread over several addresses
+// and batched (one atomic per staged flush).
+constexpr uint32_t kCandRegions = 16;
+constexpr uint32_t kFillStride = 64;   // uint32 slots between two fill counters: one 256-byte block each
+
 // Counters shared by all scopes of one pac_build_mask call.
 struct Globals {
-    uint32_t cand_total;    // candidate slots handed out
-    uint32_t list2_total;   // second-level slots handed out
-    uint32_t any_full;      // some scope did not fit the candidate list
+    uint32_t cand_total;                 // sum of cnt0 over the scopes
+    uint32_t list2_total;                // second-level slots handed out
+    uint32_t overflow;                   // candidate list unusable this call: scopes are resolved in place
     uint32_t pad;
+    uint32_t region_fill[kCandRegions * kFillStride];  // entries in region r at [r * kFillStride]
 };
 
 struct MaskScratch {
@@ -64,9 +67,9 @@ struct MaskScratch {
     uint32_t* hist0;               // [max_segments * kDigit0Bins], all zero between calls
     uint32_t* hist1;               // [max_segments * kDigit1Bins], all zero between calls
     Globals* glob;
-    unsigned long long* cand;      // [cand_cap] composites whose digit 0 is the scope's bin0
-    unsigned long long* list2;     // [cand_cap] those whose digit 1 is bin1 as well
-    uint32_t cand_cap;
+    unsigned long long* cand;      // [cand_cap] composites of undecided elements, kCandRegions regions
+    unsigned long long* list2;     // [cand_cap] those whose digit 1 is the scope's bin1 as well
+    uint32_t cand_cap;             // multiple of kCandRegions
     uint32_t* tile_sums;           // per scan tile: set bits, then exclusive offsets
 };
 

@@ -6,28 +6,32 @@
 //   hist0    one pass over the weights: per-scope histogram of digit 0 (LDS histograms,
 //            flushed to a global histogram per scope)
 //   select0  per scope: the digit-0 bin b0 that holds the k-th element, its rank inside the bin
-//   emit     second pass over the weights: mask bit = digit0 > b0 (wave ballot -> 64-bit word);
-//            elements with digit0 == b0 are undecided: their composites go to the scope's
+//   emit     second pass over the weights: mask bit = digit0 > b0, assembled into mask words in
+//            registers; elements with digit0 == b0 are undecided: their composites go to the
 //            candidate list and are counted by digit 1
 //   select1  per scope: digit-1 bin b1, rank inside it
-//   compact2 candidates whose digit 1 is b1 -> second-level list (a few hundred elements)
-//   final    one workgroup per scope resolves the remaining 37 bits on that list -> C*
+//   compact2 candidates whose digit 1 is their scope's b1 -> the scope's second-level list
+//   final    one workgroup per scope resolves the remaining bits on that list -> C*
 //   fixup    candidates with composite >= C* get their mask bit set (atomic OR)
 //   scan     exclusive prefix sum of the mask-word popcounts
 //
-// A scope whose candidates do not fit the candidate list (very many equal magnitudes) skips the
-// lists: `final` and `fixup` then walk the scope's weights instead.  Same result, slower.
+// When the undecided elements of a call do not fit the candidate list (very many equal magnitudes)
+// the lists are not used: `final` and `fixup` then walk the weights instead.  Same result, slower.
+#include <cstdlib>
+
 #include "pac_internal.h"
 
 namespace pac {
 namespace {
 
 typedef unsigned long long u64;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t key_of_bits(uint32_t bits) { return bits & 0x7FFFFFFFu; }
 __device__ __forceinline__ u64 composite_of(uint32_t key, uint32_t i) {
     return ((u64)key << 32) | (u64)(0xFFFFFFFFu - i);
 }
+__device__ __forceinline__ uint32_t index_of(u64 composite) { return 0xFFFFFFFFu - (uint32_t)composite; }
 __device__ __forceinline__ uint32_t digit0_of(uint32_t key) { return key >> kDigit0Shift; }
 __device__ __forceinline__ uint32_t digit1_of(uint32_t key) { return (key >> kDigit1Shift) & (kDigit1Bins - 1u); }
 
@@ -71,12 +75,18 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* w
     return off + inc - v;
 }
 
+// Tiles of a streaming pass are dealt to the persistent workgroups in runs of `run_len`: at any
+// time the running workgroups cover one contiguous window of the tensor.
+__device__ __forceinline__ uint32_t tile_of(uint32_t j, uint32_t run_len) {
+    return ((j / run_len) * gridDim.x + blockIdx.x) * run_len + j % run_len;
+}
+
 // ------------------------------------------------------------------------------------- hist0
 constexpr int kHistBlock = 1024;
 constexpr uint32_t kHistLoads = 4;                                 // 16-byte loads per thread per tile
 constexpr uint32_t kHistTile = kHistBlock * 4 * kHistLoads;        // 16384 elements
 
-__device__ __forceinline__ void flush_hist(uint32_t* lds, uint32_t* __restrict__ global_hist) {
+__device__ __forceinline__ void flush_hist0(uint32_t* lds, uint32_t* __restrict__ global_hist) {
     __syncthreads();
     for (uint32_t b = threadIdx.x; b < kDigit0Bins; b += kHistBlock) {
         const uint32_t v = lds[b];
@@ -92,36 +102,43 @@ template <bool VEC>
 __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restrict__ w, uint32_t n,
                                                            const SegDesc* __restrict__ seg, uint32_t nseg,
                                                            uint32_t* __restrict__ hist0, Globals* glob,
-                                                           uint32_t tiles_per_block) {
+                                                           uint32_t run_len) {
     __shared__ uint32_t lds[kDigit0Bins];
     for (uint32_t b = threadIdx.x; b < kDigit0Bins; b += kHistBlock) lds[b] = 0;
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        glob->cand_total = 0;
-        glob->list2_total = 0;
-        glob->any_full = 0;
+    if (blockIdx.x == 0) {
+        static_assert(sizeof(Globals) / 4 <= 2 * kHistBlock, "Globals cleared by one workgroup");
+        for (uint32_t j = threadIdx.x; j < sizeof(Globals) / 4; j += kHistBlock) reinterpret_cast<uint32_t*>(glob)[j] = 0;
     }
     __syncthreads();
 
     const uint32_t num_tiles = (uint32_t)(((u64)n + kHistTile - 1) / kHistTile);
-    const uint32_t t0 = blockIdx.x * tiles_per_block;
-    const uint32_t t1 = min(t0 + tiles_per_block, num_tiles);
     const uint32_t kNone = 0xFFFFFFFFu;
     uint32_t cur = kNone;   // scope whose counts sit in the LDS histogram
+    uint32_t cur_begin = 0, cur_end = 0;
 
-    for (uint32_t t = t0; t < t1; ++t) {
+    for (uint32_t j = 0;; ++j) {
+        const uint32_t t = tile_of(j, run_len);
+        if (t >= num_tiles) break;
         const uint32_t a = t * kHistTile;
         const uint32_t b = (uint32_t)min((u64)a + kHistTile, (u64)n);
-        const uint32_t s = find_seg(seg, nseg, a);
-        if (seg[s].end >= b) {
-            if (s != cur) {
-                if (cur != kNone) flush_hist(lds, hist0 + (size_t)cur * kDigit0Bins);
-                cur = s;
-            }
-            if (VEC && b - a == kHistTile) {
-                const uint4* p = reinterpret_cast<const uint4*>(w + a) + threadIdx.x;
-                uint4 v[kHistLoads];
+        const bool whole = VEC && b - a == kHistTile;
+        u32x4 v[kHistLoads];
+        if (whole) {   // streaming 16-byte loads, issued before the scope bookkeeping
+            const u32x4* p = reinterpret_cast<const u32x4*>(w + a) + threadIdx.x;
 #pragma unroll
-                for (uint32_t u = 0; u < kHistLoads; ++u) v[u] = p[u * kHistBlock];
+            for (uint32_t u = 0; u < kHistLoads; ++u) v[u] = __builtin_nontemporal_load(p + u * kHistBlock);
+        }
+        uint32_t s = cur;
+        if (cur == kNone || a < cur_begin || a >= cur_end) s = find_seg(seg, nseg, a);
+        const uint32_t s_end = s == cur ? cur_end : seg[s].end;
+        if (s_end >= b) {
+            if (s != cur) {
+                if (cur != kNone) flush_hist0(lds, hist0 + (size_t)cur * kDigit0Bins);
+                cur = s;
+                cur_begin = seg[s].begin;
+                cur_end = s_end;
+            }
+            if (whole) {
 #pragma unroll
                 for (uint32_t u = 0; u < kHistLoads; ++u) {
                     atomicAdd(&lds[digit0_of(key_of_bits(v[u].x))], 1u);
@@ -141,7 +158,7 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
             }
         }
     }
-    if (cur != kNone) flush_hist(lds, hist0 + (size_t)cur * kDigit0Bins);
+    if (cur != kNone) flush_hist0(lds, hist0 + (size_t)cur * kDigit0Bins);
 }
 
 // ---------------------------------------------------------------------------- select0 / select1
@@ -188,8 +205,7 @@ __device__ __forceinline__ bool select_bin(uint32_t* __restrict__ h, uint32_t k,
 
 __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc* __restrict__ seg,
                                                                    SegState* __restrict__ state,
-                                                                   uint32_t* __restrict__ hist0, Globals* glob,
-                                                                   uint32_t cand_cap) {
+                                                                   uint32_t* __restrict__ hist0, Globals* glob) {
     __shared__ uint32_t wave_sums[kDigit0Bins / 16 / 64];
     const uint32_t s = blockIdx.x;
     const uint32_t k = seg[s].k;
@@ -199,20 +215,19 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
     if (k == 0) {
         if (threadIdx.x == 0) {
             st->cstar = ~0ull;
-            st->bin0 = kNoBin; st->cnt0 = 0; st->krem0 = 0; st->mode = kModeNone;
-            st->cand_off = 0; st->cand_fill = 0;
+            st->active = 0;
+            st->bin0 = kNoBin; st->cnt0 = 0; st->krem0 = 0;
             st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0; st->list2_off = 0; st->list2_fill = 0;
         }
         return;
     }
     if (mine) {
-        const uint32_t off = atomicAdd(&glob->cand_total, cnt);
-        const bool fits = (u64)off + cnt <= (u64)cand_cap;
-        if (!fits) glob->any_full = 1;
         st->cstar = 0;
-        st->bin0 = bin; st->cnt0 = cnt; st->krem0 = krem; st->mode = fits ? kModeCand : kModeFull;
-        st->cand_off = fits ? off : 0; st->cand_fill = 0;
+        st->active = 1;
+        st->bin0 = bin; st->cnt0 = cnt; st->krem0 = krem;
         st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0; st->list2_off = 0; st->list2_fill = 0;
+        // The sum over scopes is at most n < 2^32, so the counter cannot wrap.
+        atomicAdd(&glob->cand_total, cnt);
     }
 }
 
@@ -221,43 +236,72 @@ __global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(SegState* __r
     __shared__ uint32_t wave_sums[kDigit1Bins / 16 / 64];
     const uint32_t s = blockIdx.x;
     SegState* st = state + s;
-    const uint32_t mode = st->mode;
-    const uint32_t k = mode == kModeNone ? 0u : st->krem0;
+    const uint32_t k = st->active ? st->krem0 : 0u;
     uint32_t bin = 0, krem = 0, cnt = 0;
     const bool mine = select_bin<(int)kDigit1Bins>(hist1 + (size_t)s * kDigit1Bins, k, wave_sums, bin, krem, cnt);
     if (mine) {
         st->bin1 = bin; st->cnt1 = cnt; st->krem1 = krem;
-        st->list2_off = mode == kModeCand ? atomicAdd(&glob->list2_total, cnt) : 0u;
+        // Slots are only used when the lists are (then sum cnt1 <= sum cnt0 <= capacity).
+        st->list2_off = atomicAdd(&glob->list2_total, cnt);
         st->list2_fill = 0;
     }
 }
 
 // -------------------------------------------------------------------------------------- emit
-// Persistent workgroups of 16 waves; a wave owns 16 consecutive mask words of a tile and loads one
-// element per lane per word, so the wave ballot of the keep predicate IS the mask word.
-// Undecided elements (digit 0 equal to the scope's bin) are rare for continuous weight
-// distributions; they are staged in LDS (composites) and counted by digit 1 in an LDS histogram,
-// and reach global memory once per workgroup and scope, so global atomics on the scope's fill
-// counter stay few.  The all-zero composite cannot occur (flat indices are below 2^32 - 1), it
+// Second pass over the weights.  With b0 the scope's digit-0 bin, lo = b0 << shift and
+// hi = (b0 + 1) << shift:   key >= hi -> kept;   lo <= key < hi -> undecided (candidate).
+//
+// Persistent workgroups of 4 waves walk 4096-element tiles, one 1024-element quarter per wave,
+// with streaming 16-byte loads.  A lane owns 4 consecutive elements, i.e. one nibble of a mask
+// word; the 8 lanes that share a 32-bit half of a mask word OR their shifted nibbles together with
+// three DPP steps and one lane stores the half word.
+// Undecided elements are rare for continuous weight distributions.  Their digit-1 counts go to a
+// workgroup LDS histogram (flushed when the workgroup leaves the scope); their composites are
+// staged in workgroup LDS and appended to one region of the candidate list with a single global
+// atomic per flush.  The all-zero composite cannot occur (flat indices are below 2^32 - 1): it
 // marks an empty staging slot.
-constexpr int kEmitBlock = 1024;
-constexpr uint32_t kEmitWordsPerWave = 16;
-constexpr uint32_t kEmitTile = (kEmitBlock / 64) * kEmitWordsPerWave * 64;   // 16384 elements
-constexpr uint32_t kStageCap = 2048;
+// Tiles that are ragged (tensor end), unaligned or cross a scope boundary take a plain path.
+constexpr int kEmitBlock = 256;
+constexpr int kEmitWaves = kEmitBlock / 64;
+constexpr uint32_t kEmitLoads = 4;                                  // 16-byte loads per lane per tile
+constexpr uint32_t kEmitWaveTile = 64 * 4 * kEmitLoads;             // 1024 elements = 16 mask words
+constexpr uint32_t kEmitTile = kEmitWaves * kEmitWaveTile;          // 4096 elements
+constexpr uint32_t kStageCap = 1024;                                // staged composites per workgroup
+constexpr uint32_t kEmitRunLen = 4;                                 // tiles per run; staging is checked per run
 
 struct EmitShared {
     u64 stage[kStageCap];
     uint32_t hist1[kDigit1Bins];
-    uint32_t wave_sums[kEmitBlock / 64];
-    uint32_t stage_count;
+    uint32_t wave_sums[kEmitWaves];
+    uint32_t stage_count;     // slots handed out (may exceed kStageCap: the excess went to global memory)
     uint32_t flush_base;
 };
 
-// Moves the staged composites of scope `s` to its candidate list.  Called by all threads.
-__device__ __forceinline__ void flush_stage(EmitShared& sh, SegState* __restrict__ st, u64* __restrict__ cand,
-                                            uint32_t cand_off) {
+__device__ __forceinline__ uint32_t or_over_8_lanes(uint32_t x) {
+    // After the three steps every lane of an aligned group of 8 holds the OR of the group.
+    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, true);   // row_half_mirror
+    return x;
+}
+
+// Reserves `count` slots in candidate region `r`; returns the first slot, or kNoSlot when the
+// region is full (the call then resolves its scopes in place).
+constexpr uint32_t kNoSlot = 0xFFFFFFFFu;
+__device__ __forceinline__ uint32_t reserve_region(Globals* glob, uint32_t r, uint32_t count, uint32_t region_cap) {
+    const uint32_t base = atomicAdd(&glob->region_fill[r * kFillStride], count);
+    if (base > region_cap || count > region_cap - base) {
+        glob->overflow = 1;
+        return kNoSlot;
+    }
+    return base;
+}
+
+// Moves the staged composites to the workgroup's candidate region.  Called by all threads.
+__device__ __forceinline__ void flush_stage(EmitShared& sh, Globals* glob, u64* __restrict__ cand, uint32_t r,
+                                            uint32_t region_cap) {
     __syncthreads();
-    if (sh.stage_count != 0) {   // uniform: read after the barrier
+    if (sh.stage_count != 0) {   // same value for every thread: nothing writes it between the barriers
         constexpr uint32_t kPer = kStageCap / kEmitBlock;
         u64 e[kPer];
         uint32_t have = 0;
@@ -268,13 +312,13 @@ __device__ __forceinline__ void flush_stage(EmitShared& sh, SegState* __restrict
         }
         uint32_t total;
         uint32_t pos = block_exclusive_scan<kEmitBlock>(have, sh.wave_sums, total);
-        if (threadIdx.x == 0) sh.flush_base = total ? atomicAdd(&st->cand_fill, total) : 0u;
+        if (threadIdx.x == 0) sh.flush_base = total ? reserve_region(glob, r, total, region_cap) : kNoSlot;
         __syncthreads();
-        pos += sh.flush_base;
+        const uint32_t base = sh.flush_base;
 #pragma unroll
         for (uint32_t j = 0; j < kPer; ++j) {
             if (e[j] != 0) {
-                cand[(size_t)cand_off + pos] = e[j];
+                if (base != kNoSlot) cand[(size_t)r * region_cap + base + pos] = e[j];
                 ++pos;
                 sh.stage[threadIdx.x * kPer + j] = 0;
             }
@@ -284,164 +328,206 @@ __device__ __forceinline__ void flush_stage(EmitShared& sh, SegState* __restrict
     __syncthreads();
 }
 
-__device__ __forceinline__ void flush_hist1(EmitShared& sh, uint32_t* __restrict__ global_hist1) {
+__device__ __forceinline__ void flush_hist1(uint32_t* lds_hist1, uint32_t* __restrict__ global_hist1) {
     __syncthreads();
     for (uint32_t b = threadIdx.x; b < kDigit1Bins; b += kEmitBlock) {
-        const uint32_t v = sh.hist1[b];
+        const uint32_t v = lds_hist1[b];
         if (v) {
             atomicAdd(&global_hist1[b], v);
-            sh.hist1[b] = 0;
+            lds_hist1[b] = 0;
         }
     }
     __syncthreads();
 }
 
+template <bool VEC>
 __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restrict__ w, uint32_t n,
                                                           const SegDesc* __restrict__ seg, uint32_t nseg,
-                                                          SegState* __restrict__ state,
+                                                          const SegState* __restrict__ state, Globals* glob,
                                                           uint32_t* __restrict__ hist1, u64* __restrict__ cand,
-                                                          u64* __restrict__ mask, uint32_t tiles_per_block) {
+                                                          uint32_t cand_cap, u64* __restrict__ mask) {
     __shared__ EmitShared sh;
-    for (uint32_t j = threadIdx.x; j < kStageCap; j += kEmitBlock) sh.stage[j] = 0;
     for (uint32_t j = threadIdx.x; j < kDigit1Bins; j += kEmitBlock) sh.hist1[j] = 0;
+    for (uint32_t j = threadIdx.x; j < kStageCap; j += kEmitBlock) sh.stage[j] = 0;
     if (threadIdx.x == 0) { sh.stage_count = 0; sh.flush_base = 0; }
     __syncthreads();
 
-    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
-    const uint32_t num_tiles = (uint32_t)(((u64)n + kEmitTile - 1) / kEmitTile);
-    const uint32_t t0 = blockIdx.x * tiles_per_block;
-    const uint32_t t1 = min(t0 + tiles_per_block, num_tiles);
-    const uint32_t kNone = 0xFFFFFFFFu;
-    uint32_t cur = kNone;                       // scope whose undecided elements sit in LDS
-    uint32_t s_bin0 = 0, s_mode = 0, s_off = 0; // of scope `cur`
+    const uint32_t lane = lane_id();
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t region = blockIdx.x % kCandRegions;
+    const uint32_t region_cap = cand_cap / kCandRegions;
+    // The number of undecided elements is known from the first pass; if they cannot fit, none is listed.
+    const bool listing = glob->cand_total <= cand_cap;
+    if (!listing && blockIdx.x == 0 && threadIdx.x == 0) glob->overflow = 1;
 
-    for (uint32_t t = t0; t < t1; ++t) {
+    const uint32_t num_tiles = (uint32_t)(((u64)n + kEmitTile - 1) / kEmitTile);
+    const uint32_t kNone = 0xFFFFFFFFu;
+    uint32_t cur = kNone;                        // scope whose digit-1 counts sit in LDS
+    uint32_t cur_begin = 0, cur_end = 0, s_lo = 0, s_hi = 0;
+
+    for (uint32_t j = 0;; ++j) {
+        const uint32_t t = tile_of(j, kEmitRunLen);
+        if (t >= num_tiles) break;
         const uint32_t a = t * kEmitTile;                               // < n
         const uint32_t b = (uint32_t)min((u64)a + kEmitTile, (u64)n);
-        const uint32_t s0 = find_seg(seg, nseg, a);
-        const bool single = seg[s0].end >= b;                           // whole tile inside one scope
-        const u64 wave_first = (u64)a + wave * (kEmitWordsPerWave * 64);
-
-        uint32_t bits[kEmitWordsPerWave];
+        const bool whole = VEC && b - a == kEmitTile;
+        const u64 wave_first = (u64)a + wave * kEmitWaveTile;
+        u32x4 v[kEmitLoads];
+        if (whole) {
+            const u32x4* p = reinterpret_cast<const u32x4*>(w + wave_first) + lane;
 #pragma unroll
-        for (uint32_t j = 0; j < kEmitWordsPerWave; ++j) {
-            const u64 i = wave_first + j * 64 + lane;
-            bits[j] = i < n ? __float_as_uint(w[i]) : 0u;
+            for (uint32_t u = 0; u < kEmitLoads; ++u) v[u] = __builtin_nontemporal_load(p + u * 64);
         }
 
-        if (single) {
-            if (s0 != cur) {
-                if (cur != kNone) {
-                    if (s_mode == kModeCand) flush_stage(sh, state + cur, cand, s_off);
-                    flush_hist1(sh, hist1 + (size_t)cur * kDigit1Bins);
-                }
-                cur = s0;
-                s_bin0 = state[s0].bin0;
-                s_mode = state[s0].mode;
-                s_off = state[s0].cand_off;
-            } else if (s_mode == kModeCand) {
-                // Read the fill level between two barriers so that every thread sees the same value.
-                __syncthreads();
-                const uint32_t staged = sh.stage_count;
-                __syncthreads();
-                if (staged >= kStageCap / 2) flush_stage(sh, state + cur, cand, s_off);
+        if (listing && j % kEmitRunLen == 0 && j != 0) {
+            // A run adds at most a few hundred composites below the listing limit; make room for it.
+            __syncthreads();
+            const uint32_t staged = sh.stage_count;
+            __syncthreads();
+            if (staged >= kStageCap / 2) flush_stage(sh, glob, cand, region, region_cap);
+        }
+
+        uint32_t s0 = cur;
+        if (cur == kNone || a < cur_begin || a >= cur_end) s0 = find_seg(seg, nseg, a);
+        const uint32_t s0_end = s0 == cur ? cur_end : seg[s0].end;
+        const bool single = s0_end >= b;                                // whole tile inside one scope
+        if (single && s0 != cur) {                                      // same decision in every wave
+            if (cur != kNone) flush_hist1(sh.hist1, hist1 + (size_t)cur * kDigit1Bins);
+            cur = s0;
+            cur_begin = seg[s0].begin;
+            cur_end = s0_end;
+            const uint32_t bin0 = state[s0].bin0;
+            s_lo = bin0 << kDigit0Shift;
+            s_hi = (bin0 + 1u) << kDigit0Shift;
+        }
+
+        if (single && whole) {
+            uint32_t und_bits = 0;   // bit 4u+e: element e of load u is undecided
+            const uint32_t width = s_hi - s_lo;
+#pragma unroll
+            for (uint32_t u = 0; u < kEmitLoads; ++u) {
+                const uint32_t k0 = key_of_bits(v[u].x), k1 = key_of_bits(v[u].y);
+                const uint32_t k2 = key_of_bits(v[u].z), k3 = key_of_bits(v[u].w);
+                const uint32_t nib = (k0 >= s_hi ? 1u : 0u) | (k1 >= s_hi ? 2u : 0u) | (k2 >= s_hi ? 4u : 0u) |
+                                     (k3 >= s_hi ? 8u : 0u);
+                const uint32_t half = or_over_8_lanes(nib << ((lane & 7u) * 4u));
+                const u64 first = wave_first + u * 256u;                // first element of this wave step
+                if ((lane & 7u) == 0)
+                    reinterpret_cast<uint32_t*>(mask)[(first >> 5) + (lane >> 3)] = half;
+                const uint32_t und = (k0 - s_lo < width ? 1u : 0u) | (k1 - s_lo < width ? 2u : 0u) |
+                                     (k2 - s_lo < width ? 4u : 0u) | (k3 - s_lo < width ? 8u : 0u);
+                und_bits |= und << (4u * u);
             }
-        }
-
-        u64 my_word = 0;
-#pragma unroll
-        for (uint32_t j = 0; j < kEmitWordsPerWave; ++j) {
-            const u64 i64 = wave_first + j * 64 + lane;
-            const bool valid = i64 < n;
-            const uint32_t i = (uint32_t)i64;
-            const uint32_t key = key_of_bits(bits[j]);
-            const uint32_t d0 = digit0_of(key);
-            if (single) {
-                const bool keep = valid && d0 > s_bin0;
-                const bool undecided = valid && d0 == s_bin0;
-                const u64 word = __ballot(keep);
-                if (lane == j) my_word = word;
-                const u64 cm = __ballot(undecided);
-                if (cm != 0) {
-                    if (undecided) atomicAdd(&sh.hist1[digit1_of(key)], 1u);
-                    if (s_mode == kModeCand) {
-                        const uint32_t cnt = (uint32_t)__popcll(cm);
-                        const uint32_t leader = (uint32_t)__ffsll((long long)cm) - 1u;
-                        uint32_t base = 0;
-                        if (lane == leader) base = atomicAdd(&sh.stage_count, cnt);
-                        base = __shfl(base, (int)leader, 64);
-                        if (base + cnt <= kStageCap) {
-                            if (undecided) sh.stage[base + lanes_below(cm)] = composite_of(key, i);
-                        } else {
-                            // staging area full: straight to the candidate list
-                            uint32_t g = 0;
-                            if (lane == leader) g = atomicAdd(&state[cur].cand_fill, cnt);
-                            g = __shfl(g, (int)leader, 64);
-                            if (undecided) cand[(size_t)s_off + g + lanes_below(cm)] = composite_of(key, i);
+            // Undecided elements, one per lane and round (a lane rarely holds more than one).
+            while (true) {
+                const bool has = und_bits != 0;
+                const u64 cm = __ballot(has);
+                if (cm == 0) break;
+                const uint32_t pick = has ? (uint32_t)__ffs((int)und_bits) - 1u : 0u;
+                und_bits &= und_bits - 1u;
+                const u32x4 q = (pick & 8u) ? ((pick & 4u) ? v[3] : v[2]) : ((pick & 4u) ? v[1] : v[0]);
+                const uint32_t raw = (pick & 2u) ? ((pick & 1u) ? q.w : q.z) : ((pick & 1u) ? q.y : q.x);
+                const uint32_t key = key_of_bits(raw);
+                if (has) atomicAdd(&sh.hist1[digit1_of(key)], 1u);
+                if (listing) {
+                    const uint32_t count = (uint32_t)__popcll(cm);
+                    const uint32_t i = (uint32_t)wave_first + (pick >> 2) * 256u + lane * 4u + (pick & 3u);
+                    uint32_t base = 0;
+                    if (lane == 0) base = atomicAdd(&sh.stage_count, count);
+                    base = __builtin_amdgcn_readfirstlane(base);
+                    if (base + count <= kStageCap) {
+                        if (has) sh.stage[base + lanes_below(cm)] = composite_of(key, i);
+                    } else {
+                        // staging area full: straight to the candidate region
+                        uint32_t g = 0;
+                        if (lane == 0) g = reserve_region(glob, region, count, region_cap);
+                        g = __builtin_amdgcn_readfirstlane(g);
+                        if (has && g != kNoSlot)
+                            cand[(size_t)region * region_cap + g + lanes_below(cm)] = composite_of(key, i);
+                    }
+                }
+            }
+        } else {
+            // Plain path: every lane handles 4 consecutive elements with its own bounds and scope lookups.
+#pragma unroll 1
+            for (uint32_t u = 0; u < kEmitLoads; ++u) {
+                const u64 first = wave_first + u * 256u;
+                uint32_t nib = 0;
+#pragma unroll 1
+                for (uint32_t e = 0; e < 4; ++e) {
+                    const u64 i64 = first + lane * 4u + e;
+                    if (i64 < n) {
+                        const uint32_t i = (uint32_t)i64;
+                        const uint32_t key = key_of_bits(__float_as_uint(w[i]));
+                        const uint32_t si = find_seg(seg, nseg, i);
+                        const uint32_t bin0 = state[si].bin0;
+                        const uint32_t d0 = digit0_of(key);
+                        if (d0 > bin0) nib |= 1u << e;
+                        if (d0 == bin0) {
+                            atomicAdd(&hist1[(size_t)si * kDigit1Bins + digit1_of(key)], 1u);
+                            if (listing) {
+                                const uint32_t g = reserve_region(glob, region, 1u, region_cap);
+                                if (g != kNoSlot) cand[(size_t)region * region_cap + g] = composite_of(key, i);
+                            }
                         }
                     }
                 }
-            } else {
-                // The tile crosses scope boundaries: every lane looks its scope up.
-                bool keep = false;
-                if (valid) {
-                    const uint32_t si = find_seg(seg, nseg, i);
-                    const uint32_t bin0 = state[si].bin0;
-                    keep = d0 > bin0;
-                    if (d0 == bin0) {
-                        atomicAdd(&hist1[(size_t)si * kDigit1Bins + digit1_of(key)], 1u);
-                        if (state[si].mode == kModeCand) {
-                            const uint32_t pos = atomicAdd(&state[si].cand_fill, 1u);
-                            cand[(size_t)state[si].cand_off + pos] = composite_of(key, i);
-                        }
-                    }
-                }
-                const u64 word = __ballot(keep);
-                if (lane == j) my_word = word;
+                const uint32_t half = or_over_8_lanes(nib << ((lane & 7u) * 4u));
+                const u64 half_idx = (first >> 5) + (lane >> 3);
+                if ((lane & 7u) == 0 && half_idx < 2 * (((u64)n + 63) >> 6))
+                    reinterpret_cast<uint32_t*>(mask)[half_idx] = half;
             }
         }
-        if (lane < kEmitWordsPerWave) {
-            const u64 word_idx = (wave_first >> 6) + lane;
-            if (word_idx * 64 < n) mask[word_idx] = my_word;
-        }
     }
-    if (cur != kNone) {
-        if (s_mode == kModeCand) flush_stage(sh, state + cur, cand, s_off);
-        flush_hist1(sh, hist1 + (size_t)cur * kDigit1Bins);
-    }
+    if (listing) flush_stage(sh, glob, cand, region, region_cap);
+    if (cur != kNone) flush_hist1(sh.hist1, hist1 + (size_t)cur * kDigit1Bins);
 }
 
 // ----------------------------------------------------------------------------------- compact2
+// Walks the candidate regions; a composite whose digit 1 equals its scope's bin goes to the scope's
+// second-level list (a few hundred entries per scope).
 constexpr int kListBlock = 256;
 
-__global__ __launch_bounds__(kListBlock) void compact2_kernel(SegState* __restrict__ state,
-                                                              const u64* __restrict__ cand,
+__global__ __launch_bounds__(kListBlock) void compact2_kernel(const SegDesc* __restrict__ seg, uint32_t nseg,
+                                                              SegState* __restrict__ state, const Globals* glob,
+                                                              const u64* __restrict__ cand, uint32_t cand_cap,
                                                               u64* __restrict__ list2) {
-    const uint32_t s = blockIdx.y;
-    SegState* st = state + s;
-    if (st->mode != kModeCand) return;
-    const uint32_t cnt0 = st->cnt0, off = st->cand_off, bin1 = st->bin1, off2 = st->list2_off;
+    if (glob->overflow) return;
+    const uint32_t r = blockIdx.y;
+    const uint32_t region_cap = cand_cap / kCandRegions;
+    const uint32_t fill = min(glob->region_fill[r * kFillStride], region_cap);
+    const u64* src = cand + (size_t)r * region_cap;
     const uint32_t lane = lane_id();
-    for (u64 base = (u64)blockIdx.x * kListBlock; base < cnt0; base += (u64)gridDim.x * kListBlock) {
+    for (u64 base = (u64)blockIdx.x * kListBlock; base < fill; base += (u64)gridDim.x * kListBlock) {
         const u64 j = base + threadIdx.x;
-        const bool valid = j < cnt0;
-        const u64 c = valid ? cand[(size_t)off + j] : 0ull;
-        const bool match = valid && digit1_of((uint32_t)(c >> 32)) == bin1;
+        const bool valid = j < fill;
+        const u64 c = valid ? src[j] : 0ull;
+        uint32_t s = 0;
+        if (valid && nseg > 1) s = find_seg(seg, nseg, index_of(c));
+        SegState* st = state + s;
+        const bool match = valid && digit1_of((uint32_t)(c >> 32)) == st->bin1;
         const u64 mm = __ballot(match);
         if (mm != 0) {
+            // one atomic per wave when all matches belong to one scope, else one per lane
             const uint32_t leader = (uint32_t)__ffsll((long long)mm) - 1u;
-            uint32_t pos = 0;
-            if (lane == leader) pos = atomicAdd(&st->list2_fill, (uint32_t)__popcll(mm));
-            pos = __shfl(pos, (int)leader, 64);
-            if (match) list2[(size_t)off2 + pos + lanes_below(mm)] = c;
+            const uint32_t s_lead = (uint32_t)__shfl((int)s, (int)leader, 64);
+            if (__ballot(match && s == s_lead) == mm) {
+                uint32_t pos = 0;
+                if (lane == leader) pos = atomicAdd(&st->list2_fill, (uint32_t)__popcll(mm));
+                pos = (uint32_t)__shfl((int)pos, (int)leader, 64);
+                if (match) list2[(size_t)st->list2_off + pos + lanes_below(mm)] = c;
+            } else if (match) {
+                const uint32_t pos = atomicAdd(&st->list2_fill, 1u);
+                list2[(size_t)st->list2_off + pos] = c;
+            }
         }
     }
 }
 
 // -------------------------------------------------------------------------------------- final
 // Resolves the low kTailBits bits of C* for one scope.  The source is either the scope's
-// second-level list (every entry already agrees with C* on digits 0 and 1) or, for a scope without
-// lists, the scope's weights filtered on the fly.
+// second-level list (every entry already agrees with C* on digits 0 and 1) or, when the lists are
+// not in use, the scope's weights filtered on the fly.
 constexpr int kFinalBlock = 256;
 
 template <bool FROM_LIST>
@@ -449,12 +535,11 @@ __device__ __forceinline__ void final_levels(const u64* __restrict__ list, uint3
                                              const float* __restrict__ w, uint32_t begin, uint32_t end,
                                              u64& prefix, uint32_t& krem, uint32_t* hist, uint32_t* wave_sums,
                                              uint32_t* found) {
-    // digit widths over the 37 tail bits, most significant first
-    const uint32_t shifts[5] = {29, 21, 13, 5, 0};
-    const uint32_t widths[5] = {8, 8, 8, 8, 5};
+    // 8-bit digits over the tail bits, most significant first; the last digit takes what is left
     uint32_t resolved_above = kTailBits;   // bits >= this position are already fixed in `prefix`
-    for (int level = 0; level < 5; ++level) {
-        const uint32_t shift = shifts[level], width = widths[level];
+    while (resolved_above > 0) {
+        const uint32_t width = resolved_above >= 8 ? 8u : resolved_above;
+        const uint32_t shift = resolved_above - width;
         hist[threadIdx.x] = 0;
         __syncthreads();
         const uint32_t count = FROM_LIST ? list_cnt : end - begin;
@@ -489,20 +574,19 @@ __device__ __forceinline__ void final_levels(const u64* __restrict__ list, uint3
 
 __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restrict__ w,
                                                             const SegDesc* __restrict__ seg,
-                                                            SegState* __restrict__ state,
+                                                            SegState* __restrict__ state, const Globals* glob,
                                                             const u64* __restrict__ list2) {
     __shared__ uint32_t hist[kFinalBlock];
     __shared__ uint32_t wave_sums[kFinalBlock / 64];
     __shared__ uint32_t found[2];
     const uint32_t s = blockIdx.x;
     SegState* st = state + s;
-    const uint32_t mode = st->mode;
-    if (mode == kModeNone) return;
+    if (!st->active) return;
     u64 prefix = ((u64)st->bin0 << (32 + kDigit0Shift)) | ((u64)st->bin1 << (32 + kDigit1Shift));
     uint32_t krem = st->krem1;
     if (threadIdx.x == 0) { found[0] = 0; found[1] = 0; }
     __syncthreads();
-    if (mode == kModeCand)
+    if (!glob->overflow)
         final_levels<true>(list2 + st->list2_off, st->cnt1, nullptr, 0, 0, prefix, krem, hist, wave_sums, found);
     else
         final_levels<false>(nullptr, 0, w, seg[s].begin, seg[s].end, prefix, krem, hist, wave_sums, found);
@@ -510,27 +594,38 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
 }
 
 // -------------------------------------------------------------------------------------- fixup
-__global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restrict__ w,
-                                                           const SegDesc* __restrict__ seg,
-                                                           const SegState* __restrict__ state,
-                                                           const u64* __restrict__ cand, u64* __restrict__ mask) {
-    const uint32_t s = blockIdx.y;
-    const SegState* st = state + s;
-    const uint32_t mode = st->mode;
-    if (mode == kModeNone) return;
-    const u64 cstar = st->cstar;
-    if (mode == kModeCand) {
-        const uint32_t cnt0 = st->cnt0, off = st->cand_off;
-        for (u64 j = (u64)blockIdx.x * kListBlock + threadIdx.x; j < cnt0; j += (u64)gridDim.x * kListBlock) {
-            const u64 c = cand[(size_t)off + j];
-            if (c >= cstar) {
-                const uint32_t i = 0xFFFFFFFFu - (uint32_t)c;
-                atomicOr(&mask[i >> 6], 1ull << (i & 63u));
-            }
+// Undecided elements at or above their scope's C* are kept: set their mask bits.
+__global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restrict__ w, uint32_t n,
+                                                           const SegDesc* __restrict__ seg, uint32_t nseg,
+                                                           const SegState* __restrict__ state, const Globals* glob,
+                                                           const u64* __restrict__ cand, uint32_t cand_cap,
+                                                           u64* __restrict__ mask) {
+    if (!glob->overflow) {
+        const uint32_t r = blockIdx.y;
+        const uint32_t region_cap = cand_cap / kCandRegions;
+        const uint32_t fill = min(glob->region_fill[r * kFillStride], region_cap);
+        const u64* src = cand + (size_t)r * region_cap;
+        for (u64 j = (u64)blockIdx.x * kListBlock + threadIdx.x; j < fill; j += (u64)gridDim.x * kListBlock) {
+            const u64 c = src[j];
+            const uint32_t i = index_of(c);
+            const uint32_t s = nseg > 1 ? find_seg(seg, nseg, i) : 0u;
+            if (c >= state[s].cstar) atomicOr(&mask[i >> 6], 1ull << (i & 63u));
         }
     } else {
-        const uint32_t begin = seg[s].begin, end = seg[s].end, bin0 = st->bin0;
-        for (u64 i = (u64)begin + (u64)blockIdx.x * kListBlock + threadIdx.x; i < end; i += (u64)gridDim.x * kListBlock) {
+        // Lists not in use: walk the weights.
+        const u64 tid = ((u64)blockIdx.y * gridDim.x + blockIdx.x) * kListBlock + threadIdx.x;
+        const u64 nthreads = (u64)gridDim.x * gridDim.y * kListBlock;
+        const uint32_t kNone = 0xFFFFFFFFu;
+        uint32_t s = kNone, s_begin = 0, s_end = 0, bin0 = 0;
+        u64 cstar = 0;
+        for (u64 i = tid; i < n; i += nthreads) {
+            if (s == kNone || i < s_begin || i >= s_end) {
+                s = find_seg(seg, nseg, (uint32_t)i);
+                s_begin = seg[s].begin;
+                s_end = seg[s].end;
+                bin0 = state[s].bin0;
+                cstar = state[s].cstar;
+            }
             const uint32_t key = key_of_bits(__float_as_uint(w[i]));
             if (digit0_of(key) == bin0 && composite_of(key, (uint32_t)i) >= cstar)
                 atomicOr(&mask[i >> 6], 1ull << (i & 63u));
@@ -609,48 +704,57 @@ __global__ __launch_bounds__(kScanBlock) void scan_write_prefix_kernel(const u64
 
 inline uint32_t div_up_u64(u64 a, u64 b) { return (uint32_t)((a + b - 1) / b); }
 
+// Workgroups of a persistent kernel that fit on the device at once.
+template <typename K>
+uint32_t resident_blocks(K kernel, int block, int num_cu, uint32_t fallback_per_cu) {
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, block, 0) != hipSuccess || per_cu <= 0)
+        per_cu = (int)fallback_per_cu;
+    return (uint32_t)per_cu * (uint32_t)num_cu;
+}
+
 }  // namespace
 
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
                              unsigned long long* d_mask, uint32_t* d_prefix, int num_cu, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     const uint32_t words = div_up_u64(n, 64);
+    const bool aligned = (reinterpret_cast<uintptr_t>(d_weights) & 15u) == 0;
 
-    // hist0: persistent workgroups, each walks a contiguous run of tiles
     {
         const uint32_t num_tiles = div_up_u64(n, kHistTile);
-        const uint32_t want = (uint32_t)num_cu * 2u;
-        const uint32_t blocks = num_tiles < want ? num_tiles : want;
-        const uint32_t per = div_up_u64(num_tiles, blocks);
-        const uint32_t grid = div_up_u64(num_tiles, per);
-        if ((reinterpret_cast<uintptr_t>(d_weights) & 15u) == 0)
+        static const uint32_t want = resident_blocks(hist0_kernel<true>, kHistBlock, num_cu, 2);
+        const uint32_t grid = num_tiles < want ? num_tiles : want;
+        const uint32_t run_len = 4;
+        if (aligned)
             hipLaunchKernelGGL((hist0_kernel<true>), dim3(grid), dim3(kHistBlock), 0, stream, d_weights, n, s.seg,
-                               nseg, s.hist0, s.glob, per);
+                               nseg, s.hist0, s.glob, run_len);
         else
             hipLaunchKernelGGL((hist0_kernel<false>), dim3(grid), dim3(kHistBlock), 0, stream, d_weights, n, s.seg,
-                               nseg, s.hist0, s.glob, per);
+                               nseg, s.hist0, s.glob, run_len);
     }
     hipLaunchKernelGGL(select0_kernel, dim3(nseg), dim3(kDigit0Bins / 16), 0, stream, s.seg, s.state, s.hist0,
-                       s.glob, s.cand_cap);
+                       s.glob);
     {
         const uint32_t num_tiles = div_up_u64(n, kEmitTile);
-        const uint32_t want = (uint32_t)num_cu * 2u;
-        const uint32_t blocks = num_tiles < want ? num_tiles : want;
-        const uint32_t per = div_up_u64(num_tiles, blocks);
-        const uint32_t grid = div_up_u64(num_tiles, per);
-        hipLaunchKernelGGL(emit_kernel, dim3(grid), dim3(kEmitBlock), 0, stream, d_weights, n, s.seg, nseg, s.state,
-                           s.hist1, s.cand, d_mask, per);
+        static const uint32_t want = resident_blocks(emit_kernel<true>, kEmitBlock, num_cu, 4);
+        const uint32_t grid = num_tiles < want ? num_tiles : want;
+        if (aligned)
+            hipLaunchKernelGGL((emit_kernel<true>), dim3(grid), dim3(kEmitBlock), 0, stream, d_weights, n, s.seg,
+                               nseg, s.state, s.glob, s.hist1, s.cand, s.cand_cap, d_mask);
+        else
+            hipLaunchKernelGGL((emit_kernel<false>), dim3(grid), dim3(kEmitBlock), 0, stream, d_weights, n, s.seg,
+                               nseg, s.state, s.glob, s.hist1, s.cand, s.cand_cap, d_mask);
     }
     hipLaunchKernelGGL(select1_kernel, dim3(nseg), dim3(kDigit1Bins / 16), 0, stream, s.state, s.hist1, s.glob);
 
-    uint32_t per_seg_blocks = 16384u / nseg;
-    if (per_seg_blocks < 1) per_seg_blocks = 1;
-    if (per_seg_blocks > 256) per_seg_blocks = 256;
-    hipLaunchKernelGGL(compact2_kernel, dim3(per_seg_blocks, nseg), dim3(kListBlock), 0, stream, s.state, s.cand,
+    const uint32_t list_blocks = 64;   // per candidate region
+    hipLaunchKernelGGL(compact2_kernel, dim3(list_blocks, kCandRegions), dim3(kListBlock), 0, stream, s.seg, nseg,
+                       s.state, s.glob, s.cand, s.cand_cap, s.list2);
+    hipLaunchKernelGGL(final_kernel, dim3(nseg), dim3(kFinalBlock), 0, stream, d_weights, s.seg, s.state, s.glob,
                        s.list2);
-    hipLaunchKernelGGL(final_kernel, dim3(nseg), dim3(kFinalBlock), 0, stream, d_weights, s.seg, s.state, s.list2);
-    hipLaunchKernelGGL(fixup_kernel, dim3(per_seg_blocks, nseg), dim3(kListBlock), 0, stream, d_weights, s.seg,
-                       s.state, s.cand, d_mask);
+    hipLaunchKernelGGL(fixup_kernel, dim3(list_blocks, kCandRegions), dim3(kListBlock), 0, stream, d_weights, n,
+                       s.seg, nseg, s.state, s.glob, s.cand, s.cand_cap, d_mask);
 
     const uint32_t scan_tiles = div_up_u64(words, kScanTile);
     hipLaunchKernelGGL(scan_tile_sums_kernel, dim3(scan_tiles), dim3(kScanBlock), 0, stream, d_mask, words,
