@@ -14,7 +14,7 @@ namespace {
 
 constexpr int kRing = 4;               // pinned staging slots for the segment table
 constexpr uint32_t kMaxSegments = 65535;   // scopes index a grid dimension
-constexpr uint64_t kScanTileWords = 2048;  // must match the scan kernels' tile
+constexpr uint64_t kScanTileWords = 2048;  // not larger than the scan kernel's tile
 
 thread_local char g_create_error[256] = "";
 
@@ -77,8 +77,9 @@ void free_scratch(pac_ctx* ctx) {
     (void)hipFree(s.hist1);
     (void)hipFree(s.glob);
     (void)hipFree(s.cand);
-    (void)hipFree(s.list2);
-    (void)hipFree(s.tile_sums);
+    (void)hipFree(s.match);
+    (void)hipFree(s.match_count);
+    (void)hipFree(s.tile_state);
     for (int i = 0; i < kRing; ++i) {
         if (ctx->h_ring[i]) (void)hipHostFree(ctx->h_ring[i]);
         if (ctx->ring_event[i]) (void)hipEventDestroy(ctx->ring_event[i]);
@@ -164,8 +165,9 @@ pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_
     alloc((void**)&s.hist1, hist1_bytes);
     alloc((void**)&s.glob, sizeof(pac::Globals));
     alloc((void**)&s.cand, (size_t)cap * sizeof(unsigned long long));
-    alloc((void**)&s.list2, (size_t)cap * sizeof(unsigned long long));
-    alloc((void**)&s.tile_sums, (size_t)(scan_tiles + 1) * sizeof(uint32_t));
+    alloc((void**)&s.match, (size_t)pac::kMatchSlots * sizeof(unsigned long long));
+    alloc((void**)&s.match_count, (size_t)pac::kMatchBlocks * sizeof(uint32_t));
+    alloc((void**)&s.tile_state, (size_t)(scan_tiles + 1) * sizeof(unsigned long long));
     for (int i = 0; ok && i < kRing; ++i) {
         hipError_t r = hipHostMalloc((void**)&ctx->h_ring[i], (size_t)max_segments * sizeof(pac::SegDesc), hipHostMallocDefault);
         if (r == hipSuccess) r = hipEventCreateWithFlags(&ctx->ring_event[i], hipEventDisableTiming);

@@ -41,9 +41,7 @@ struct SegState {
     uint32_t bin1;             // digit 1 of cstar
     uint32_t cnt1;             // candidates whose digit 1 equals bin1
     uint32_t krem1;            // rank of the k-th element among those
-    uint32_t list2_off;        // first slot of this scope in the second-level list
-    uint32_t list2_fill;       // slots filled so far
-    uint32_t pad;
+    uint32_t pad[3];
 };
 
 // The candidate list is split into regions with one fill counter each: an atomic on one address
@@ -52,12 +50,20 @@ struct SegState {
 constexpr uint32_t kCandRegions = 16;
 constexpr uint32_t kFillStride = 64;   // uint32 slots between two fill counters: one 256-byte block each
 
+// compact2 runs with a fixed number of workgroups, each owning a short list of matches.
+constexpr uint32_t kMatchBlocksPerRegion = 64;
+constexpr uint32_t kMatchBlocks = kMatchBlocksPerRegion * kCandRegions;      // 1024
+constexpr uint32_t kMatchSlotsPerBlock = 64;
+constexpr uint32_t kMatchSlots = kMatchBlocks * kMatchSlotsPerBlock;         // 65536
+
 // Counters shared by all scopes of one pac_build_mask call.
 struct Globals {
     uint32_t cand_total;                 // sum of cnt0 over the scopes
-    uint32_t list2_total;                // second-level slots handed out
+    uint32_t match_overflow;             // a workgroup of compact2 ran out of match slots
     uint32_t overflow;                   // candidate list unusable this call: scopes are resolved in place
-    uint32_t pad;
+    uint32_t scan_ticket;                // next tile of the prefix scan
+    uint32_t scan_stalled;               // set if a scan workgroup gave up waiting (never expected)
+    uint32_t pad[3];
     uint32_t region_fill[kCandRegions * kFillStride];  // entries in region r at [r * kFillStride]
 };
 
@@ -68,9 +74,11 @@ struct MaskScratch {
     uint32_t* hist1;               // [max_segments * kDigit1Bins], all zero between calls
     Globals* glob;
     unsigned long long* cand;      // [cand_cap] composites of undecided elements, kCandRegions regions
-    unsigned long long* list2;     // [cand_cap] those whose digit 1 is the scope's bin1 as well
+    unsigned long long* match;     // [kMatchSlots] candidates whose digit 1 is their scope's bin1 as well,
+                                   // kMatchSlotsPerBlock slots per workgroup of compact2
+    uint32_t* match_count;         // [kMatchBlocks] slots used by each workgroup
     uint32_t cand_cap;             // multiple of kCandRegions
-    uint32_t* tile_sums;           // per scan tile: set bits, then exclusive offsets
+    unsigned long long* tile_state; // per scan tile: status and running count of the look-back scan
 };
 
 // Launchers (defined in pac_mask.hip / pac_pack.hip).  All enqueue on `stream` and return the

@@ -10,8 +10,9 @@
 //            registers; elements with digit0 == b0 are undecided: their composites go to the
 //            candidate list and are counted by digit 1
 //   select1  per scope: digit-1 bin b1, rank inside it
-//   compact2 candidates whose digit 1 is their scope's b1 -> the scope's second-level list
-//   final    one workgroup per scope resolves the remaining bits on that list -> C*
+//   compact2 candidates whose digit 1 is their scope's b1 -> match lists (a few hundred per scope)
+//   final    one workgroup per scope gathers its matches into LDS and resolves the remaining
+//            bits there -> C*
 //   fixup    candidates with composite >= C* get their mask bit set (atomic OR)
 //   scan     exclusive prefix sum of the mask-word popcounts
 //
@@ -217,7 +218,7 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
             st->cstar = ~0ull;
             st->active = 0;
             st->bin0 = kNoBin; st->cnt0 = 0; st->krem0 = 0;
-            st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0; st->list2_off = 0; st->list2_fill = 0;
+            st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
         }
         return;
     }
@@ -225,14 +226,14 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
         st->cstar = 0;
         st->active = 1;
         st->bin0 = bin; st->cnt0 = cnt; st->krem0 = krem;
-        st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0; st->list2_off = 0; st->list2_fill = 0;
+        st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
         // The sum over scopes is at most n < 2^32, so the counter cannot wrap.
         atomicAdd(&glob->cand_total, cnt);
     }
 }
 
 __global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(SegState* __restrict__ state,
-                                                                   uint32_t* __restrict__ hist1, Globals* glob) {
+                                                                   uint32_t* __restrict__ hist1) {
     __shared__ uint32_t wave_sums[kDigit1Bins / 16 / 64];
     const uint32_t s = blockIdx.x;
     SegState* st = state + s;
@@ -241,9 +242,6 @@ __global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(SegState* __r
     const bool mine = select_bin<(int)kDigit1Bins>(hist1 + (size_t)s * kDigit1Bins, k, wave_sums, bin, krem, cnt);
     if (mine) {
         st->bin1 = bin; st->cnt1 = cnt; st->krem1 = krem;
-        // Slots are only used when the lists are (then sum cnt1 <= sum cnt0 <= capacity).
-        st->list2_off = atomicAdd(&glob->list2_total, cnt);
-        st->list2_fill = 0;
     }
 }
 
@@ -484,54 +482,53 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
 }
 
 // ----------------------------------------------------------------------------------- compact2
-// Walks the candidate regions; a composite whose digit 1 equals its scope's bin goes to the scope's
-// second-level list (a few hundred entries per scope).
+// Walks the candidate regions; a composite whose digit 1 equals its scope's bin is a match.  There
+// are only a few hundred matches per scope, and an append counter shared by all workgroups would
+// cost one serialised global atomic per match; instead every workgroup collects its matches in LDS
+// and writes them to slots of its own, with their number, for `final` to pick up.
 constexpr int kListBlock = 256;
 
 __global__ __launch_bounds__(kListBlock) void compact2_kernel(const SegDesc* __restrict__ seg, uint32_t nseg,
-                                                              SegState* __restrict__ state, const Globals* glob,
+                                                              const SegState* __restrict__ state, Globals* glob,
                                                               const u64* __restrict__ cand, uint32_t cand_cap,
-                                                              u64* __restrict__ list2) {
-    if (glob->overflow) return;
-    const uint32_t r = blockIdx.y;
-    const uint32_t region_cap = cand_cap / kCandRegions;
-    const uint32_t fill = min(glob->region_fill[r * kFillStride], region_cap);
-    const u64* src = cand + (size_t)r * region_cap;
-    const uint32_t lane = lane_id();
-    for (u64 base = (u64)blockIdx.x * kListBlock; base < fill; base += (u64)gridDim.x * kListBlock) {
-        const u64 j = base + threadIdx.x;
-        const bool valid = j < fill;
-        const u64 c = valid ? src[j] : 0ull;
-        uint32_t s = 0;
-        if (valid && nseg > 1) s = find_seg(seg, nseg, index_of(c));
-        SegState* st = state + s;
-        const bool match = valid && digit1_of((uint32_t)(c >> 32)) == st->bin1;
-        const u64 mm = __ballot(match);
-        if (mm != 0) {
-            // one atomic per wave when all matches belong to one scope, else one per lane
-            const uint32_t leader = (uint32_t)__ffsll((long long)mm) - 1u;
-            const uint32_t s_lead = (uint32_t)__shfl((int)s, (int)leader, 64);
-            if (__ballot(match && s == s_lead) == mm) {
-                uint32_t pos = 0;
-                if (lane == leader) pos = atomicAdd(&st->list2_fill, (uint32_t)__popcll(mm));
-                pos = (uint32_t)__shfl((int)pos, (int)leader, 64);
-                if (match) list2[(size_t)st->list2_off + pos + lanes_below(mm)] = c;
-            } else if (match) {
-                const uint32_t pos = atomicAdd(&st->list2_fill, 1u);
-                list2[(size_t)st->list2_off + pos] = c;
+                                                              u64* __restrict__ match,
+                                                              uint32_t* __restrict__ match_count) {
+    __shared__ u64 found[kMatchSlotsPerBlock];
+    __shared__ uint32_t nfound;
+    const uint32_t block_id = blockIdx.y * gridDim.x + blockIdx.x;   // < kMatchBlocks by the launch shape
+    if (threadIdx.x == 0) nfound = 0;
+    __syncthreads();
+    if (!glob->overflow) {
+        const uint32_t r = blockIdx.y;
+        const uint32_t region_cap = cand_cap / kCandRegions;
+        const uint32_t fill = min(glob->region_fill[r * kFillStride], region_cap);
+        const u64* src = cand + (size_t)r * region_cap;
+        for (u64 j = (u64)blockIdx.x * kListBlock + threadIdx.x; j < fill; j += (u64)gridDim.x * kListBlock) {
+            const u64 c = src[j];
+            const uint32_t s = nseg > 1 ? find_seg(seg, nseg, index_of(c)) : 0u;
+            if (digit1_of((uint32_t)(c >> 32)) == state[s].bin1) {
+                const uint32_t pos = atomicAdd(&nfound, 1u);
+                if (pos < kMatchSlotsPerBlock) found[pos] = c;
             }
         }
     }
+    __syncthreads();
+    const uint32_t total = nfound;
+    if (total > kMatchSlotsPerBlock && threadIdx.x == 0) glob->match_overflow = 1;   // `final` uses the weights
+    const uint32_t kept = min(total, kMatchSlotsPerBlock);
+    if (threadIdx.x < kept) match[(size_t)block_id * kMatchSlotsPerBlock + threadIdx.x] = found[threadIdx.x];
+    if (threadIdx.x == 0) match_count[block_id] = kept;
 }
 
 // -------------------------------------------------------------------------------------- final
-// Resolves the low kTailBits bits of C* for one scope.  The source is either the scope's
-// second-level list (every entry already agrees with C* on digits 0 and 1) or, when the lists are
-// not in use, the scope's weights filtered on the fly.
-constexpr int kFinalBlock = 256;
+// Resolves the low kTailBits bits of C* for one scope.  The source is the scope's matches, gathered
+// from the match slots into LDS (every one agrees with C* on digits 0 and 1), or, when the lists
+// are not usable, the scope's weights filtered on the fly.
+constexpr int kFinalBlock = 1024;
+constexpr uint32_t kFinalList = 4096;   // matches of one scope that fit in LDS
 
 template <bool FROM_LIST>
-__device__ __forceinline__ void final_levels(const u64* __restrict__ list, uint32_t list_cnt,
+__device__ __forceinline__ void final_levels(const u64* list, uint32_t list_cnt,
                                              const float* __restrict__ w, uint32_t begin, uint32_t end,
                                              u64& prefix, uint32_t& krem, uint32_t* hist, uint32_t* wave_sums,
                                              uint32_t* found) {
@@ -540,7 +537,7 @@ __device__ __forceinline__ void final_levels(const u64* __restrict__ list, uint3
     while (resolved_above > 0) {
         const uint32_t width = resolved_above >= 8 ? 8u : resolved_above;
         const uint32_t shift = resolved_above - width;
-        hist[threadIdx.x] = 0;
+        if (threadIdx.x < 256) hist[threadIdx.x] = 0;
         __syncthreads();
         const uint32_t count = FROM_LIST ? list_cnt : end - begin;
         for (u64 j = threadIdx.x; j < count; j += kFinalBlock) {
@@ -555,8 +552,8 @@ __device__ __forceinline__ void final_levels(const u64* __restrict__ list, uint3
                 atomicAdd(&hist[(uint32_t)(c >> shift) & ((1u << width) - 1u)], 1u);
         }
         __syncthreads();
-        // thread t owns bin t; walk from the highest bin down
-        const uint32_t v = hist[threadIdx.x];
+        // thread t < 256 owns bin t; walk from the highest bin down
+        const uint32_t v = threadIdx.x < 256 ? hist[threadIdx.x] : 0u;
         uint32_t total;
         const uint32_t below = block_exclusive_scan<kFinalBlock>(v, wave_sums, total);
         const uint32_t above = total - below - v;
@@ -575,21 +572,41 @@ __device__ __forceinline__ void final_levels(const u64* __restrict__ list, uint3
 __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restrict__ w,
                                                             const SegDesc* __restrict__ seg,
                                                             SegState* __restrict__ state, const Globals* glob,
-                                                            const u64* __restrict__ list2) {
-    __shared__ uint32_t hist[kFinalBlock];
+                                                            const u64* __restrict__ match,
+                                                            const uint32_t* __restrict__ match_count) {
+    __shared__ u64 list[kFinalList];
+    __shared__ uint32_t hist[256];
     __shared__ uint32_t wave_sums[kFinalBlock / 64];
     __shared__ uint32_t found[2];
+    __shared__ uint32_t gathered;
     const uint32_t s = blockIdx.x;
     SegState* st = state + s;
     if (!st->active) return;
     u64 prefix = ((u64)st->bin0 << (32 + kDigit0Shift)) | ((u64)st->bin1 << (32 + kDigit1Shift));
     uint32_t krem = st->krem1;
-    if (threadIdx.x == 0) { found[0] = 0; found[1] = 0; }
+    const uint32_t begin = seg[s].begin, end = seg[s].end;
+    const uint32_t cnt1 = st->cnt1;
+    if (threadIdx.x == 0) { found[0] = 0; found[1] = 0; gathered = 0; }
     __syncthreads();
-    if (!glob->overflow)
-        final_levels<true>(list2 + st->list2_off, st->cnt1, nullptr, 0, 0, prefix, krem, hist, wave_sums, found);
-    else
-        final_levels<false>(nullptr, 0, w, seg[s].begin, seg[s].end, prefix, krem, hist, wave_sums, found);
+    const bool from_list = !glob->overflow && !glob->match_overflow && cnt1 <= kFinalList;
+    if (from_list) {
+        // Matches of this scope: thread t looks through the slots of compact2's workgroup t.
+        static_assert(kFinalBlock == (int)kMatchBlocks, "one thread per compact2 workgroup");
+        const uint32_t mine = min(match_count[threadIdx.x], kMatchSlotsPerBlock);
+        for (uint32_t e = 0; e < mine; ++e) {
+            const u64 c = match[(size_t)threadIdx.x * kMatchSlotsPerBlock + e];
+            const uint32_t i = index_of(c);
+            if (i >= begin && i < end) {
+                const uint32_t pos = atomicAdd(&gathered, 1u);
+                if (pos < kFinalList) list[pos] = c;
+            }
+        }
+        __syncthreads();
+        const uint32_t count = min(gathered, kFinalList);
+        final_levels<true>(list, count, nullptr, 0, 0, prefix, krem, hist, wave_sums, found);
+    } else {
+        final_levels<false>(nullptr, 0, w, begin, end, prefix, krem, hist, wave_sums, found);
+    }
     if (threadIdx.x == 0) st->cstar = prefix;
 }
 
@@ -599,7 +616,12 @@ __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restri
                                                            const SegDesc* __restrict__ seg, uint32_t nseg,
                                                            const SegState* __restrict__ state, const Globals* glob,
                                                            const u64* __restrict__ cand, uint32_t cand_cap,
-                                                           u64* __restrict__ mask) {
+                                                           u64* __restrict__ mask, u64* __restrict__ tile_state,
+                                                           uint32_t scan_tiles) {
+    // The scan that follows starts from cleared tile states.
+    for (u64 j = ((u64)blockIdx.y * gridDim.x + blockIdx.x) * kListBlock + threadIdx.x; j < scan_tiles;
+         j += (u64)gridDim.x * gridDim.y * kListBlock)
+        tile_state[j] = 0;
     if (!glob->overflow) {
         const uint32_t r = blockIdx.y;
         const uint32_t region_cap = cand_cap / kCandRegions;
@@ -634,71 +656,139 @@ __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restri
 }
 
 // --------------------------------------------------------------------------------------- scan
-// prefix[j] = number of set bits in mask words 0..j-1.  Three small kernels over the mask words:
-// per-tile popcount sums, one workgroup scanning the tile sums, per-tile rescan with the offset.
-constexpr int kScanBlock = 256;
-constexpr uint32_t kScanWordsPerThread = 8;
-constexpr uint32_t kScanTile = kScanBlock * kScanWordsPerThread;   // 2048 words
+// prefix[j] = number of set bits in mask words 0..j-1: a single-pass scan with decoupled
+// look-back.  A workgroup takes the next tile from a ticket counter (so every tile before it is
+// owned by a workgroup that is already running), publishes the tile's bit count, then walks back
+// over its predecessors' published values until it meets one that already holds an inclusive
+// prefix.  Status and value share one 64-bit word, read and written with device-scope atomics, so
+// no other data needs ordering across the XCDs' L2 caches.  The wait for a predecessor is bounded:
+// a workgroup that gives up raises `scan_stalled` and finishes (with wrong offsets) rather than spin.
+constexpr int kScanBlock = 1024;
+constexpr int kScanWaves = kScanBlock / 64;
+constexpr uint32_t kScanIters = 16;                                  // 16-byte loads per lane
+constexpr uint32_t kScanWaveWords = 64 * 2 * kScanIters;             // 2048 words per wave
+constexpr uint32_t kScanTile = kScanWaves * kScanWaveWords;          // 32768 words
+constexpr u64 kTileAggregate = 1ull << 32;   // value = bits in this tile
+constexpr u64 kTileInclusive = 2ull << 32;   // value = bits in this tile and all before it
+constexpr uint32_t kScanSpinLimit = 1u << 22;
 
-__device__ __forceinline__ void load_words(const u64* __restrict__ mask, uint32_t words, uint32_t first,
-                                           uint32_t pc[kScanWordsPerThread]) {
+__device__ __forceinline__ u64 tile_load(const u64* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void tile_store(u64* p, u64 v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
 #pragma unroll
-    for (uint32_t j = 0; j < kScanWordsPerThread; ++j) {
-        const u64 idx = (u64)first + j;
-        pc[j] = idx < words ? (uint32_t)__popcll(mask[idx]) : 0u;
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+    const uint32_t lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(v, d, 64);
+        if (lane >= (uint32_t)d) v += t;
     }
+    return v;
 }
 
-__global__ __launch_bounds__(kScanBlock) void scan_tile_sums_kernel(const u64* __restrict__ mask, uint32_t words,
-                                                                    uint32_t* __restrict__ tile_sums) {
-    __shared__ uint32_t wave_sums[kScanBlock / 64];
-    uint32_t pc[kScanWordsPerThread];
-    load_words(mask, words, blockIdx.x * kScanTile + threadIdx.x * kScanWordsPerThread, pc);
-    uint32_t sum = 0;
+__global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __restrict__ mask, uint32_t words,
+                                                                   u64* __restrict__ tile_state, Globals* glob,
+                                                                   uint32_t* __restrict__ prefix) {
+    __shared__ uint32_t ex_lds[kScanIters][kScanBlock];
+    __shared__ uint32_t wave_totals[kScanWaves];
+    __shared__ uint32_t sh_tile, sh_base;
+    if (threadIdx.x == 0) sh_tile = atomicAdd(&glob->scan_ticket, 1u);
+    __syncthreads();
+    const uint32_t tile = sh_tile;
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+
+    // A lane owns two consecutive words per iteration (one 16-byte load); a wave 2048 consecutive words.
+    const u64 wave_first = (u64)tile * kScanTile + wave * kScanWaveWords;
+    uint32_t pp[kScanIters];   // popcounts of the lane's two words, packed: low byte first word, next byte second
 #pragma unroll
-    for (uint32_t j = 0; j < kScanWordsPerThread; ++j) sum += pc[j];
-    uint32_t total;
-    block_exclusive_scan<kScanBlock>(sum, wave_sums, total);
-    if (threadIdx.x == 0) tile_sums[blockIdx.x] = total;
-}
-
-constexpr int kScanTopBlock = 1024;
-__global__ __launch_bounds__(kScanTopBlock) void scan_tile_offsets_kernel(uint32_t* __restrict__ tile_sums,
-                                                                          uint32_t num_tiles) {
-    __shared__ uint32_t wave_sums[kScanTopBlock / 64];
-    const uint32_t per = (num_tiles + kScanTopBlock - 1) / kScanTopBlock;
-    const uint32_t first = threadIdx.x * per;
-    uint32_t sum = 0;
-    for (uint32_t j = 0; j < per; ++j)
-        if (first + j < num_tiles) sum += tile_sums[first + j];
-    uint32_t total;
-    uint32_t run = block_exclusive_scan<kScanTopBlock>(sum, wave_sums, total);
-    for (uint32_t j = 0; j < per; ++j) {
-        if (first + j < num_tiles) {
-            const uint32_t v = tile_sums[first + j];
-            tile_sums[first + j] = run;
-            run += v;
+    for (uint32_t it = 0; it < kScanIters; ++it) {
+        const u64 w0 = wave_first + it * 128u + lane * 2u;
+        if (w0 + 1 < words) {
+            const ulonglong2 v = *reinterpret_cast<const ulonglong2*>(mask + w0);
+            pp[it] = (uint32_t)__popcll(v.x) | ((uint32_t)__popcll(v.y) << 8);
+        } else {
+            pp[it] = w0 < words ? (uint32_t)__popcll(mask[w0]) : 0u;
         }
     }
-}
+    // ex_lds[it][thread]: bits before the lane's first word, within the wave's chunk (parked in LDS
+    // to keep the register count of a 16-wave workgroup down)
+    uint32_t running = 0;
+#pragma unroll
+    for (uint32_t it = 0; it < kScanIters; ++it) {
+        const uint32_t s = (pp[it] & 0xFFu) + (pp[it] >> 8);
+        const uint32_t inc = wave_inclusive_scan(s);
+        ex_lds[it][threadIdx.x] = running + inc - s;
+        running += (uint32_t)__shfl((int)inc, 63, 64);
+    }
+    if (lane == 0) wave_totals[wave] = running;
+    __syncthreads();
+    uint32_t wave_off = 0, tile_total = 0;
+#pragma unroll
+    for (int i = 0; i < kScanWaves; ++i) {
+        const uint32_t x = wave_totals[i];
+        if ((uint32_t)i < wave) wave_off += x;
+        tile_total += x;
+    }
 
-__global__ __launch_bounds__(kScanBlock) void scan_write_prefix_kernel(const u64* __restrict__ mask, uint32_t words,
-                                                                       const uint32_t* __restrict__ tile_offsets,
-                                                                       uint32_t* __restrict__ prefix) {
-    __shared__ uint32_t wave_sums[kScanBlock / 64];
-    uint32_t pc[kScanWordsPerThread];
-    const uint32_t first = blockIdx.x * kScanTile + threadIdx.x * kScanWordsPerThread;
-    load_words(mask, words, first, pc);
-    uint32_t sum = 0;
+    if (threadIdx.x < 64) {   // wave 0 publishes and looks back
+        if (tile == 0) {
+            if (lane == 0) {
+                tile_store(&tile_state[0], kTileInclusive | tile_total);
+                sh_base = 0;
+            }
+        } else {
+            if (lane == 0) tile_store(&tile_state[tile], kTileAggregate | tile_total);
+            uint32_t before = 0;          // bits in the tiles walked so far
+            uint32_t window = tile;       // lanes look at tiles window-1, window-2, ...
+            bool stalled = false;
+            while (true) {
+                const bool real = lane < window;
+                const u64* slot = &tile_state[real ? window - 1 - lane : 0];
+                u64 st = real ? tile_load(slot) : kTileInclusive;   // "before tile 0": inclusive 0
+                uint32_t spins = 0;
+                while (__any((st >> 32) == 0)) {
+                    if ((st >> 32) == 0) st = tile_load(slot);
+                    if (++spins > kScanSpinLimit) { stalled = true; break; }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                if (stalled) break;
+                const u64 incl = __ballot((st >> 32) == 2);
+                if (incl != 0) {
+                    const uint32_t stop = (uint32_t)__ffsll((long long)incl) - 1u;   // nearest inclusive tile
+                    before += wave_sum(lane <= stop ? (uint32_t)st : 0u);
+                    break;
+                }
+                before += wave_sum((uint32_t)st);
+                window -= 64;
+            }
+            if (lane == 0) {
+                if (stalled) glob->scan_stalled = 1;
+                tile_store(&tile_state[tile], kTileInclusive | (u64)(before + tile_total));
+                sh_base = before;
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t base = sh_base + wave_off;
 #pragma unroll
-    for (uint32_t j = 0; j < kScanWordsPerThread; ++j) sum += pc[j];
-    uint32_t total;
-    uint32_t run = tile_offsets[blockIdx.x] + block_exclusive_scan<kScanBlock>(sum, wave_sums, total);
-#pragma unroll
-    for (uint32_t j = 0; j < kScanWordsPerThread; ++j) {
-        const u64 idx = (u64)first + j;
-        if (idx < words) prefix[idx] = run;
-        run += pc[j];
+    for (uint32_t it = 0; it < kScanIters; ++it) {
+        const u64 w0 = wave_first + it * 128u + lane * 2u;
+        const uint32_t a = base + ex_lds[it][threadIdx.x];
+        if (w0 + 1 < words) {
+            *reinterpret_cast<uint2*>(prefix + w0) = make_uint2(a, a + (pp[it] & 0xFFu));
+        } else if (w0 < words) {
+            prefix[w0] = a;
+        }
     }
 }
 
@@ -746,22 +836,21 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
             hipLaunchKernelGGL((emit_kernel<false>), dim3(grid), dim3(kEmitBlock), 0, stream, d_weights, n, s.seg,
                                nseg, s.state, s.glob, s.hist1, s.cand, s.cand_cap, d_mask);
     }
-    hipLaunchKernelGGL(select1_kernel, dim3(nseg), dim3(kDigit1Bins / 16), 0, stream, s.state, s.hist1, s.glob);
+    hipLaunchKernelGGL(select1_kernel, dim3(nseg), dim3(kDigit1Bins / 16), 0, stream, s.state, s.hist1);
 
-    const uint32_t list_blocks = 64;   // per candidate region
-    hipLaunchKernelGGL(compact2_kernel, dim3(list_blocks, kCandRegions), dim3(kListBlock), 0, stream, s.seg, nseg,
-                       s.state, s.glob, s.cand, s.cand_cap, s.list2);
+    const uint32_t list_blocks = 256;   // per candidate region
+    static_assert(kListBlock == 256, "compact2 runs 4 waves per workgroup");
+    hipLaunchKernelGGL(compact2_kernel, dim3(kMatchBlocksPerRegion, kCandRegions), dim3(kListBlock), 0, stream,
+                       s.seg, nseg, s.state, s.glob, s.cand, s.cand_cap, s.match, s.match_count);
     hipLaunchKernelGGL(final_kernel, dim3(nseg), dim3(kFinalBlock), 0, stream, d_weights, s.seg, s.state, s.glob,
-                       s.list2);
+                       s.match, s.match_count);
     hipLaunchKernelGGL(fixup_kernel, dim3(list_blocks, kCandRegions), dim3(kListBlock), 0, stream, d_weights, n,
-                       s.seg, nseg, s.state, s.glob, s.cand, s.cand_cap, d_mask);
+                       s.seg, nseg, s.state, s.glob, s.cand, s.cand_cap, d_mask, s.tile_state,
+                       div_up_u64(words, kScanTile));
 
     const uint32_t scan_tiles = div_up_u64(words, kScanTile);
-    hipLaunchKernelGGL(scan_tile_sums_kernel, dim3(scan_tiles), dim3(kScanBlock), 0, stream, d_mask, words,
-                       s.tile_sums);
-    hipLaunchKernelGGL(scan_tile_offsets_kernel, dim3(1), dim3(kScanTopBlock), 0, stream, s.tile_sums, scan_tiles);
-    hipLaunchKernelGGL(scan_write_prefix_kernel, dim3(scan_tiles), dim3(kScanBlock), 0, stream, d_mask, words,
-                       s.tile_sums, d_prefix);
+    hipLaunchKernelGGL(scan_lookback_kernel, dim3(scan_tiles), dim3(kScanBlock), 0, stream, d_mask, words,
+                       s.tile_state, s.glob, d_prefix);
     return hipGetLastError();
 }
 
