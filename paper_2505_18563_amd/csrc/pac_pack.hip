@@ -45,13 +45,14 @@ __device__ __forceinline__ uint16_t elem_of<uint16_t>(const uint4& v, int e) {
 }
 
 // ------------------------------------------------------------------------- tile geometry
-// One wave owns a tile of U*64 chunks = U*E mask words.  Because a tile starts on a mask-word
-// boundary, its first compact slot S0 and the slot after its last survivor S1 are two entries of the
-// prefix array (S1 = nnz for the tile that holds the end of the tensor): wave-uniform values, read
-// with scalar loads, no cross-lane reduction.  Survivors are staged in the wave's LDS region at
-// (slot - S0 + phase), where phase makes LDS 16-byte chunks line up with 16-byte chunks of the
-// compact buffer; the compact range is then moved with at most one head, one tail (element-wise)
-// and ceil(T/64E) full 16-byte accesses per lane.  No workgroup barrier is involved.
+// A tile is a run of chunks that starts on a mask-word boundary, so its first compact slot S0 and
+// the slot after its last survivor S1 are two entries of the prefix array (S1 = nnz for the tile that
+// holds the end of the tensor): uniform values, read with scalar loads, no cross-lane reduction.
+// Survivors are staged in LDS at (slot - S0 + phase), where phase makes LDS 16-byte chunks line up
+// with 16-byte chunks of the compact buffer; the compact range is then moved with at most one head,
+// one tail (element-wise) and full 16-byte accesses in between.
+// Scatter (decompress) uses one wave per tile (kPackU * 64 chunks) and no workgroup barrier;
+// gather (compress) uses one workgroup per tile, see below.
 constexpr int kPackBlock = 128;
 constexpr int kPackWaves = kPackBlock / 64;
 constexpr int kPackU = 2;
@@ -79,19 +80,31 @@ __device__ __forceinline__ uint32_t phase_of(const T* p) {
 }
 
 // ------------------------------------------------------------------------------------ compress
-template <typename T, int U>
-__global__ __launch_bounds__(kPackBlock) void compress_tile_kernel(const u32x4* __restrict__ grad, uint32_t n,
-                                                                   const unsigned long long* __restrict__ mask,
-                                                                   const uint32_t* __restrict__ prefix,
-                                                                   T* __restrict__ compact, uint32_t nnz) {
-    typedef Tile<T, U> G;
-    constexpr uint32_t E = G::E;
-    __shared__ __attribute__((aligned(16))) T stage[kPackWaves][G::kStage];
+// One workgroup (4 waves) per tile of kCompressU * 256 chunks; the tile's survivors form one
+// contiguous compact range, staged in LDS and written out cooperatively after one barrier, so that
+// only the two ends of a ~0.8 KB range are partial cache lines.
+constexpr int kCompressBlock = 256;
+constexpr int kCompressU = 2;
 
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t tile = blockIdx.x * kPackWaves + wave;
-    if ((unsigned long long)tile * G::kElems >= n) return;
+template <typename T, int U>
+struct BlockTile {
+    static constexpr uint32_t E = 16 / sizeof(T);
+    static constexpr uint32_t kChunks = kCompressBlock * U;
+    static constexpr uint32_t kElems = kChunks * E;
+    static constexpr uint32_t kWords = kElems / 64;
+    static constexpr uint32_t kStage = kElems + 2 * E;    // + phase + tail elements
+};
+
+template <typename T, int U>
+__global__ __launch_bounds__(kCompressBlock) void compress_tile_kernel(const u32x4* __restrict__ grad, uint32_t n,
+                                                                       const unsigned long long* __restrict__ mask,
+                                                                       const uint32_t* __restrict__ prefix,
+                                                                       T* __restrict__ compact, uint32_t nnz) {
+    typedef BlockTile<T, U> G;
+    constexpr uint32_t E = G::E;
+    __shared__ __attribute__((aligned(16))) T stage[G::kStage];
+
+    const uint32_t tile = blockIdx.x;
     const uint32_t n_chunks = n / E;
     const uint32_t words = (uint32_t)(((unsigned long long)n + 63) >> 6);
     const uint32_t chunk0 = tile * G::kChunks;
@@ -101,7 +114,7 @@ __global__ __launch_bounds__(kPackBlock) void compress_tile_kernel(const u32x4* 
     uint32_t pre[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint32_t q = chunk0 + (uint32_t)u * 64 + lane;
+        const uint32_t q = chunk0 + (uint32_t)u * kCompressBlock + threadIdx.x;
         word[u] = 0;
         pre[u] = 0;
         v[u] = (u32x4){0, 0, 0, 0};
@@ -113,24 +126,24 @@ __global__ __launch_bounds__(kPackBlock) void compress_tile_kernel(const u32x4* 
         }
     }
 
-    const uint32_t w0 = tile * G::kWords;
+    const uint32_t w0 = tile * G::kWords;   // < words by the launch shape
     const uint32_t w1 = w0 + G::kWords;
     const uint32_t s0 = prefix[w0];
     const uint32_t s1 = w1 < words ? prefix[w1] : nnz;
-    // A mask/prefix/nnz triple that does not fit together must not make the kernel write out of bounds.
+    // A mask/prefix/nnz triple that does not fit together must not make the kernel write out of
+    // bounds.  (Same decision in every thread, so the barrier below is safe.)
     if (s0 > s1 || s1 > nnz || s1 - s0 > G::kElems) return;
     const uint32_t count = s1 - s0;
     const uint32_t ph = phase_of(compact + s0);
-    T* my = stage[wave];
 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint32_t q = chunk0 + (uint32_t)u * 64 + lane;
+        const uint32_t q = chunk0 + (uint32_t)u * kCompressBlock + threadIdx.x;
         const uint32_t bitoff = (q * E) & 63u;
         uint32_t sub = (uint32_t)(word[u] >> bitoff) & ((1u << E) - 1u);
         const uint32_t pos = pre[u] + popc64(word[u] & ((1ull << bitoff) - 1ull)) - s0 + ph;
         if (pos > G::kStage - E) sub = 0;
-        T* p = my + pos;
+        T* p = stage + pos;
         const uint4 vv = make_uint4(v[u].x, v[u].y, v[u].z, v[u].w);
 #pragma unroll
         for (int e = 0; e < (int)E; ++e) {
@@ -142,28 +155,28 @@ __global__ __launch_bounds__(kPackBlock) void compress_tile_kernel(const u32x4* 
     }
     // Elements after the last whole chunk (n not a multiple of E) belong to the tile they follow.
     if (tile == n_chunks / G::kChunks) {
-        const uint32_t i = n_chunks * E + lane;
-        if (lane < E && i < n) {
+        const uint32_t i = n_chunks * E + threadIdx.x;
+        if (threadIdx.x < E && i < n) {
             const unsigned long long wd = mask[i >> 6];
             if ((wd >> (i & 63u)) & 1ull) {
                 const uint32_t pos = prefix[i >> 6] + popc64(wd & ((1ull << (i & 63u)) - 1ull)) - s0 + ph;
-                if (pos < G::kStage) my[pos] = reinterpret_cast<const T*>(grad)[i];
+                if (pos < G::kStage) stage[pos] = reinterpret_cast<const T*>(grad)[i];
             }
         }
     }
-    wave_lds_sync();
+    __syncthreads();
 
     // LDS [ph, ph + count) -> compact [s0, s1); (compact + s0 - ph) is 16-byte aligned.
     T* gbase = compact + s0 - ph;
     const uint32_t a = ph, b = ph + count;
     uint32_t h_end = (a + E - 1u) & ~(E - 1u);
     if (h_end > b) h_end = b;
-    if (lane < h_end - a) gbase[a + lane] = my[a + lane];
-    for (uint32_t c = h_end / E + lane; c < b / E; c += 64)
-        *reinterpret_cast<u32x4*>(gbase + c * E) = *reinterpret_cast<const u32x4*>(my + c * E);
+    if (threadIdx.x < h_end - a) gbase[a + threadIdx.x] = stage[a + threadIdx.x];
+    for (uint32_t c = h_end / E + threadIdx.x; c < b / E; c += kCompressBlock)
+        *reinterpret_cast<u32x4*>(gbase + c * E) = *reinterpret_cast<const u32x4*>(stage + c * E);
     uint32_t t0 = b & ~(E - 1u);
     if (t0 < h_end) t0 = h_end;
-    if (lane < b - t0) gbase[t0 + lane] = my[t0 + lane];
+    if (threadIdx.x < b - t0) gbase[t0 + threadIdx.x] = stage[t0 + threadIdx.x];
 }
 
 // Any element alignment: one element per lane, lane b of a wave owns bit b of one mask word.
@@ -425,14 +438,14 @@ hipError_t launch_compress(const void* d_grad, int dtype, uint32_t n, const unsi
     if (n == 0) return hipSuccess;
     if (aligned16(d_grad)) {
         if (dtype == 0) {
-            const uint32_t tiles = div_up(n, Tile<uint32_t, kPackU>::kElems);
-            hipLaunchKernelGGL((compress_tile_kernel<uint32_t, kPackU>), dim3(div_up(tiles, kPackWaves)),
-                               dim3(kPackBlock), 0, stream, static_cast<const u32x4*>(d_grad), n, d_mask, d_prefix,
+            const uint32_t tiles = div_up(n, BlockTile<uint32_t, kCompressU>::kElems);
+            hipLaunchKernelGGL((compress_tile_kernel<uint32_t, kCompressU>), dim3(tiles), dim3(kCompressBlock), 0,
+                               stream, static_cast<const u32x4*>(d_grad), n, d_mask, d_prefix,
                                static_cast<uint32_t*>(d_compact), nnz);
         } else {
-            const uint32_t tiles = div_up(n, Tile<uint16_t, kPackU>::kElems);
-            hipLaunchKernelGGL((compress_tile_kernel<uint16_t, kPackU>), dim3(div_up(tiles, kPackWaves)),
-                               dim3(kPackBlock), 0, stream, static_cast<const u32x4*>(d_grad), n, d_mask, d_prefix,
+            const uint32_t tiles = div_up(n, BlockTile<uint16_t, kCompressU>::kElems);
+            hipLaunchKernelGGL((compress_tile_kernel<uint16_t, kCompressU>), dim3(tiles), dim3(kCompressBlock), 0,
+                               stream, static_cast<const u32x4*>(d_grad), n, d_mask, d_prefix,
                                static_cast<uint16_t*>(d_compact), nnz);
         }
     } else {
