@@ -69,12 +69,21 @@ bool is_aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t
 
 uint32_t elem_size(pac_dtype dt) { return dt == PAC_F32 ? 4u : 2u; }
 
+// Stride of the sampled histogram pass over one prune scope: scopes below 8M elements are counted
+// in full; larger ones keep at least about 4M sampled elements, at most one 16384-element tile in 16.
+uint32_t sample_stride(uint64_t len) {
+    uint32_t stride = 1;
+    while (stride < 16 && len / (2ull * stride) >= (1ull << 22)) stride *= 2;
+    return stride;
+}
+
 void free_scratch(pac_ctx* ctx) {
     pac::MaskScratch& s = ctx->scratch;
     (void)hipFree(s.seg);
     (void)hipFree(s.state);
     (void)hipFree(s.hist0);
     (void)hipFree(s.hist1);
+    (void)hipFree(s.kept_above);
     (void)hipFree(s.glob);
     (void)hipFree(s.cand);
     (void)hipFree(s.match);
@@ -163,6 +172,7 @@ pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_
     alloc((void**)&s.state, (size_t)max_segments * sizeof(pac::SegState));
     alloc((void**)&s.hist0, hist0_bytes);
     alloc((void**)&s.hist1, hist1_bytes);
+    alloc((void**)&s.kept_above, (size_t)max_segments * pac::kCandRegions * pac::kFillStride * sizeof(uint32_t));
     alloc((void**)&s.glob, sizeof(pac::Globals));
     alloc((void**)&s.cand, (size_t)cap * sizeof(unsigned long long));
     alloc((void**)&s.match, (size_t)pac::kMatchSlots * sizeof(unsigned long long));
@@ -241,12 +251,13 @@ pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n, cons
 
     // Keep counts: host arithmetic, so the total is known without waiting for the device.
     std::vector<pac::SegDesc> table(nseg);
-    uint64_t total = 0;
+    uint64_t total = 0, sampled = 0;
     for (uint32_t s = 0; s < nseg; ++s) {
         const uint64_t b = h_seg_offsets[s], e = h_seg_offsets[s + 1];
         const uint64_t k = pac_keep_count(e - b, h_sparsity[s]);
-        table[s] = pac::SegDesc{(uint32_t)b, (uint32_t)e, (uint32_t)k, 0u};
+        table[s] = pac::SegDesc{(uint32_t)b, (uint32_t)e, (uint32_t)k, sample_stride(e - b)};
         total += k;
+        sampled += (e - b) / table[s].stride;
     }
     if (h_nnz_out) *h_nnz_out = total;
     if (n == 0) return PAC_OK;
@@ -279,7 +290,7 @@ pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n, cons
         ctx->table_valid = true;
     }
 
-    hipError_t r = pac::launch_build_mask(ctx->scratch, d_weights, (uint32_t)n, nseg,
+    hipError_t r = pac::launch_build_mask(ctx->scratch, d_weights, (uint32_t)n, nseg, sampled,
                                           reinterpret_cast<unsigned long long*>(d_mask), d_prefix, ctx->num_cu, stream);
     if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_build_mask: launch: %s", hipGetErrorString(r));
     return PAC_OK;

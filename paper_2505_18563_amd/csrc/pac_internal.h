@@ -9,37 +9,39 @@ namespace pac {
 // ---- magnitude order ------------------------------------------------------------------------
 // key(w) = bit pattern with the sign cleared (31 bits).  Elements of a prune scope are ordered by
 // the 63-bit composite (key << 32) | (0xFFFFFFFF - flat_index): larger composite = kept first,
-// i.e. |w| descending, flat index ascending.  The selection resolves the composite of the k-th
-// element digit by digit:
-//   digit 0: key bits 30..17 (14 bits, one pass over the weights)
-//   digit 1: key bits 16..6  (11 bits, counted while the candidates of digit 0 are collected)
-//   tail   : key bits 5..0 and the 32 index bits (38 bits, resolved inside one workgroup)
+// i.e. |w| descending, flat index ascending.  The selection finds the composite C* of the k-th
+// element in three steps:
+//   bracket: a key range [lo, hi) that holds the k-th key, made of whole bins of digit 0
+//            (key bits 30..17) taken from a histogram over all, or a sample of, the scope's elements
+//   digit 1: the undecided elements (lo <= key < hi) are counted by (key - lo) >> sh1 while they
+//            are collected; the bin of the k-th among them narrows the range to 2^sh1 keys
+//   tail   : the remaining sh1 key bits and the 32 index bits, resolved inside one workgroup
 constexpr uint32_t kDigit0Bits = 14;
 constexpr uint32_t kDigit0Bins = 1u << kDigit0Bits;   // 16384
 constexpr uint32_t kDigit0Shift = 17;                 // within the 31-bit key
 constexpr uint32_t kDigit1Bits = 11;
 constexpr uint32_t kDigit1Bins = 1u << kDigit1Bits;   // 2048
-constexpr uint32_t kDigit1Shift = kDigit0Shift - kDigit1Bits;   // 6, within the 31-bit key
-constexpr uint32_t kTailBits = 32 + kDigit1Shift;     // composite bits below digit 1
-constexpr uint32_t kNoBin = kDigit0Bins;              // "no element is kept": above every digit
+constexpr uint32_t kKeyEnd = 0x80000000u;             // one past the largest key
 
 // One prune scope, written by the host.
 struct SegDesc {
-    uint32_t begin;   // first flat element
-    uint32_t end;     // one past the last flat element
-    uint32_t k;       // keep count
-    uint32_t pad;
+    uint32_t begin;    // first flat element
+    uint32_t end;      // one past the last flat element
+    uint32_t k;        // keep count
+    uint32_t stride;   // the first histogram pass visits one tile in `stride` (power of two; 1 = every tile)
 };
 
 // Selection state of one prune scope, device only.
 struct SegState {
     unsigned long long cstar;  // composite of the k-th element: kept iff composite >= cstar
-    uint32_t active;           // 0 if k == 0 (nothing kept, nothing to resolve)
-    uint32_t bin0;             // digit 0 of cstar (kNoBin if k == 0)
-    uint32_t cnt0;             // elements of the scope whose digit 0 equals bin0
-    uint32_t krem0;            // rank of the k-th element among them (1-based, descending)
-    uint32_t bin1;             // digit 1 of cstar
-    uint32_t cnt1;             // candidates whose digit 1 equals bin1
+    uint32_t active;           // 0 if nothing is undecided (k == 0 or k == n): cstar is already final
+    uint32_t lo;               // bracket: key >= hi is kept, lo <= key < hi is undecided
+    uint32_t hi;
+    uint32_t sh1;              // digit 1 of an undecided key = (key - lo) >> sh1, below kDigit1Bins
+    uint32_t exact;            // the histogram counted every element, so krem0 was known before emit
+    uint32_t krem0;            // rank of the k-th element among the undecided ones (1-based, descending)
+    uint32_t bin1;             // digit 1 of the k-th element
+    uint32_t cnt1;             // undecided elements with that digit
     uint32_t krem1;            // rank of the k-th element among those
     uint32_t pad[3];
 };
@@ -58,12 +60,13 @@ constexpr uint32_t kMatchSlots = kMatchBlocks * kMatchSlotsPerBlock;         // 
 
 // Counters shared by all scopes of one pac_build_mask call.
 struct Globals {
-    uint32_t cand_total;                 // sum of cnt0 over the scopes
+    unsigned long long cand_total;       // (estimated) undecided elements over all scopes
+    uint32_t retry;                      // a sampled bracket missed the k-th element: redo with full counts
     uint32_t match_overflow;             // a workgroup of compact2 ran out of match slots
     uint32_t overflow;                   // candidate list unusable this call: scopes are resolved in place
     uint32_t scan_ticket;                // next tile of the prefix scan
     uint32_t scan_stalled;               // set if a scan workgroup gave up waiting (never expected)
-    uint32_t pad[3];
+    uint32_t pad[2];
     uint32_t region_fill[kCandRegions * kFillStride];  // entries in region r at [r * kFillStride]
 };
 
@@ -72,6 +75,8 @@ struct MaskScratch {
     SegState* state;               // [max_segments]
     uint32_t* hist0;               // [max_segments * kDigit0Bins], all zero between calls
     uint32_t* hist1;               // [max_segments * kDigit1Bins], all zero between calls
+    uint32_t* kept_above;          // [max_segments * kCandRegions * kFillStride] elements with key >= hi,
+                                   // one padded counter per scope and candidate region
     Globals* glob;
     unsigned long long* cand;      // [cand_cap] composites of undecided elements, kCandRegions regions
     unsigned long long* match;     // [kMatchSlots] candidates whose digit 1 is their scope's bin1 as well,
@@ -83,8 +88,10 @@ struct MaskScratch {
 
 // Launchers (defined in pac_mask.hip / pac_pack.hip).  All enqueue on `stream` and return the
 // first launch error.
+// `sampled_elems`: elements the first histogram pass visits (sum over scopes of length / stride).
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
-                             unsigned long long* d_mask, uint32_t* d_prefix, int num_cu, hipStream_t stream);
+                             uint64_t sampled_elems, unsigned long long* d_mask, uint32_t* d_prefix, int num_cu,
+                             hipStream_t stream);
 
 hipError_t launch_compress(const void* d_grad, int dtype, uint32_t n, const unsigned long long* d_mask,
                            const uint32_t* d_prefix, void* d_compact, uint32_t nnz, hipStream_t stream);

@@ -1,20 +1,24 @@
 // pac_build_mask: magnitude threshold at a target sparsity -> bitmask + exclusive prefix index.
 //
-// Per prune scope the kept set is "the k largest composites" (see pac_internal.h).  The k-th
-// composite C* is found by a most-significant-digit radix select:
+// Per prune scope the kept set is "the k largest composites" (see pac_internal.h); C* is the k-th.
 //
-//   hist0    one pass over the weights: per-scope histogram of digit 0 (LDS histograms,
-//            flushed to a global histogram per scope)
-//   select0  per scope: the digit-0 bin b0 that holds the k-th element, its rank inside the bin
-//   emit     second pass over the weights: mask bit = digit0 > b0, assembled into mask words in
-//            registers; elements with digit0 == b0 are undecided: their composites go to the
-//            candidate list and are counted by digit 1
-//   select1  per scope: digit-1 bin b1, rank inside it
+//   hist0    histogram of digit 0 per scope (LDS histograms flushed to a global one).  Large scopes
+//            are only sampled: one 16384-element tile in `stride`, at a hashed position
+//   select0  per scope: bracket [lo, hi) of whole digit-0 bins that holds the k-th key - exactly
+//            one bin when every element was counted, the bins inside a confidence band around the
+//            estimated rank when the scope was sampled
+//   emit     one pass over the weights: mask bit = key >= hi, assembled into mask words in
+//            registers; elements with lo <= key < hi are undecided: their composites go to the
+//            candidate list and are counted by digit 1; kept elements are counted per scope
+//   select1  per scope: checks that the bracket did hold the k-th key (always true for exact
+//            counts), then the digit-1 bin b1 of the k-th undecided element and its rank inside
+//   (retry)  if a sampled bracket missed, hist0/select0/emit/select1 run again with full counts;
+//            otherwise those four launches return at once
 //   compact2 candidates whose digit 1 is their scope's b1 -> match lists (a few hundred per scope)
 //   final    one workgroup per scope gathers its matches into LDS and resolves the remaining
 //            bits there -> C*
 //   fixup    candidates with composite >= C* get their mask bit set (atomic OR)
-//   scan     exclusive prefix sum of the mask-word popcounts
+//   scan     exclusive prefix sum of the mask-word popcounts (single pass, decoupled look-back)
 //
 // When the undecided elements of a call do not fit the candidate list (very many equal magnitudes)
 // the lists are not used: `final` and `fixup` then walk the weights instead.  Same result, slower.
@@ -34,11 +38,27 @@ __device__ __forceinline__ u64 composite_of(uint32_t key, uint32_t i) {
 }
 __device__ __forceinline__ uint32_t index_of(u64 composite) { return 0xFFFFFFFFu - (uint32_t)composite; }
 __device__ __forceinline__ uint32_t digit0_of(uint32_t key) { return key >> kDigit0Shift; }
-__device__ __forceinline__ uint32_t digit1_of(uint32_t key) { return (key >> kDigit1Shift) & (kDigit1Bins - 1u); }
+__device__ __forceinline__ uint32_t hash32(uint32_t x) {
+    x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+    return x;
+}
+// Whether the sampled histogram pass visits tile t at stride m (a power of two): one tile of every
+// aligned group of m, at a hashed position so that no period of the tensor layout can line up with it.
+__device__ __forceinline__ bool tile_sampled(uint32_t t, uint32_t m) {
+    if (m <= 1) return true;
+    const uint32_t group = t >> (31 - __clz((int)m));   // t / m
+    return (t & (m - 1)) == (hash32(group) & (m - 1));
+}
 
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
 __device__ __forceinline__ uint32_t lanes_below(u64 m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
 }
 
 // First scope whose end exceeds flat index i (scopes ascending; empty scopes are never returned).
@@ -78,8 +98,9 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* w
 
 // Tiles of a streaming pass are dealt to the persistent workgroups in runs of `run_len`: at any
 // time the running workgroups cover one contiguous window of the tensor.
-__device__ __forceinline__ uint32_t tile_of(uint32_t j, uint32_t run_len) {
-    return ((j / run_len) * gridDim.x + blockIdx.x) * run_len + j % run_len;
+constexpr uint32_t kRunLen = 4;
+__device__ __forceinline__ uint32_t tile_of(uint32_t j) {
+    return ((j / kRunLen) * gridDim.x + blockIdx.x) * kRunLen + j % kRunLen;
 }
 
 // ------------------------------------------------------------------------------------- hist0
@@ -103,43 +124,48 @@ template <bool VEC>
 __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restrict__ w, uint32_t n,
                                                            const SegDesc* __restrict__ seg, uint32_t nseg,
                                                            uint32_t* __restrict__ hist0, Globals* glob,
-                                                           uint32_t run_len) {
+                                                           uint32_t pass) {
     __shared__ uint32_t lds[kDigit0Bins];
+    if (pass != 0 && !glob->retry) return;             // the retry pass has nothing to do
     for (uint32_t b = threadIdx.x; b < kDigit0Bins; b += kHistBlock) lds[b] = 0;
     if (blockIdx.x == 0) {
+        // Counters of this call start from zero (the retry pass keeps `retry` itself).
         static_assert(sizeof(Globals) / 4 <= 2 * kHistBlock, "Globals cleared by one workgroup");
-        for (uint32_t j = threadIdx.x; j < sizeof(Globals) / 4; j += kHistBlock) reinterpret_cast<uint32_t*>(glob)[j] = 0;
+        uint32_t* g = reinterpret_cast<uint32_t*>(glob);
+        const uint32_t keep = pass != 0 ? (uint32_t)(offsetof(Globals, retry) / 4) : 0xFFFFFFFFu;
+        for (uint32_t j = threadIdx.x; j < sizeof(Globals) / 4; j += kHistBlock)
+            if (j != keep) g[j] = 0;
     }
     __syncthreads();
 
     const uint32_t num_tiles = (uint32_t)(((u64)n + kHistTile - 1) / kHistTile);
     const uint32_t kNone = 0xFFFFFFFFu;
     uint32_t cur = kNone;   // scope whose counts sit in the LDS histogram
-    uint32_t cur_begin = 0, cur_end = 0;
+    uint32_t cur_begin = 0, cur_end = 0, cur_stride = 1;
 
     for (uint32_t j = 0;; ++j) {
-        const uint32_t t = tile_of(j, run_len);
+        const uint32_t t = tile_of(j);
         if (t >= num_tiles) break;
         const uint32_t a = t * kHistTile;
         const uint32_t b = (uint32_t)min((u64)a + kHistTile, (u64)n);
-        const bool whole = VEC && b - a == kHistTile;
-        u32x4 v[kHistLoads];
-        if (whole) {   // streaming 16-byte loads, issued before the scope bookkeeping
-            const u32x4* p = reinterpret_cast<const u32x4*>(w + a) + threadIdx.x;
-#pragma unroll
-            for (uint32_t u = 0; u < kHistLoads; ++u) v[u] = __builtin_nontemporal_load(p + u * kHistBlock);
-        }
         uint32_t s = cur;
         if (cur == kNone || a < cur_begin || a >= cur_end) s = find_seg(seg, nseg, a);
         const uint32_t s_end = s == cur ? cur_end : seg[s].end;
         if (s_end >= b) {
+            const uint32_t stride = pass != 0 ? 1u : (s == cur ? cur_stride : seg[s].stride);
             if (s != cur) {
                 if (cur != kNone) flush_hist0(lds, hist0 + (size_t)cur * kDigit0Bins);
                 cur = s;
                 cur_begin = seg[s].begin;
                 cur_end = s_end;
+                cur_stride = stride;
             }
-            if (whole) {
+            if (!tile_sampled(t, stride)) continue;
+            if (VEC && b - a == kHistTile) {
+                const u32x4* p = reinterpret_cast<const u32x4*>(w + a) + threadIdx.x;
+                u32x4 v[kHistLoads];
+#pragma unroll
+                for (uint32_t u = 0; u < kHistLoads; ++u) v[u] = __builtin_nontemporal_load(p + u * kHistBlock);
 #pragma unroll
                 for (uint32_t u = 0; u < kHistLoads; ++u) {
                     atomicAdd(&lds[digit0_of(key_of_bits(v[u].x))], 1u);
@@ -152,10 +178,12 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
                     atomicAdd(&lds[digit0_of(key_of_bits(__float_as_uint(w[i])))], 1u);
             }
         } else {
-            // The tile crosses scope boundaries: count element by element into the global histograms.
+            // The tile crosses scope boundaries: element by element into the global histograms,
+            // each element under its own scope's sampling rule.
             for (u64 i = (u64)a + threadIdx.x; i < b; i += kHistBlock) {
                 const uint32_t si = find_seg(seg, nseg, (uint32_t)i);
-                atomicAdd(&hist0[(size_t)si * kDigit0Bins + digit0_of(key_of_bits(__float_as_uint(w[i])))], 1u);
+                if (pass != 0 || tile_sampled(t, seg[si].stride))
+                    atomicAdd(&hist0[(size_t)si * kDigit0Bins + digit0_of(key_of_bits(__float_as_uint(w[i])))], 1u);
             }
         }
     }
@@ -204,50 +232,165 @@ __device__ __forceinline__ bool select_bin(uint32_t* __restrict__ h, uint32_t k,
     return mine;
 }
 
+__device__ __forceinline__ uint32_t ceil_log2(uint32_t x) { return x <= 1 ? 0u : 32u - (uint32_t)__clz((int)(x - 1)); }
+
+// Width of the confidence band around the estimated sample rank, in standard deviations of a
+// simple random sample.  Tiles are clusters, which can inflate the variance; a bracket that misses
+// is detected after emit and the call falls back to full counts.
+constexpr double kBandSigmas = 8.0;
+
 __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc* __restrict__ seg,
                                                                    SegState* __restrict__ state,
-                                                                   uint32_t* __restrict__ hist0, Globals* glob) {
-    __shared__ uint32_t wave_sums[kDigit0Bins / 16 / 64];
+                                                                   uint32_t* __restrict__ hist0,
+                                                                   uint32_t* __restrict__ kept_above, Globals* glob,
+                                                                   uint32_t pass) {
+    constexpr int THREADS = kDigit0Bins / 16;
+    __shared__ uint32_t wave_sums[THREADS / 64];
+    __shared__ uint32_t sh_hi, sh_lo, sh_above_hi, sh_in_range;
+    if (pass != 0 && !glob->retry) return;
     const uint32_t s = blockIdx.x;
     const uint32_t k = seg[s].k;
-    uint32_t bin = 0, krem = 0, cnt = 0;
-    const bool mine = select_bin<(int)kDigit0Bins>(hist0 + (size_t)s * kDigit0Bins, k, wave_sums, bin, krem, cnt);
+    const uint32_t n_s = seg[s].end - seg[s].begin;
     SegState* st = state + s;
-    if (k == 0) {
+
+    // this scope's kept counters start from zero
+    for (uint32_t j = threadIdx.x; j < kCandRegions * kFillStride; j += THREADS)
+        kept_above[(size_t)s * kCandRegions * kFillStride + j] = 0;
+
+    // thread t owns bins [16t, 16t+16); read and clear them
+    uint32_t loc[16];
+    uint4* hv = reinterpret_cast<uint4*>(hist0 + (size_t)s * kDigit0Bins) + threadIdx.x * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint4 x = hv[j];
+        loc[4 * j] = x.x; loc[4 * j + 1] = x.y; loc[4 * j + 2] = x.z; loc[4 * j + 3] = x.w;
+        hv[j] = make_uint4(0, 0, 0, 0);
+    }
+    uint32_t sum = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) sum += loc[j];
+    uint32_t counted;   // elements the histogram pass visited
+    const uint32_t below = block_exclusive_scan<THREADS>(sum, wave_sums, counted);
+    const uint32_t above = counted - below - sum;   // elements in bins owned by higher threads
+
+    if (k == 0 || k == n_s) {
+        // Nothing to resolve: keep nothing (hi above every key) or everything (hi = 0).
         if (threadIdx.x == 0) {
-            st->cstar = ~0ull;
+            st->cstar = k == 0 ? ~0ull : 0ull;
             st->active = 0;
-            st->bin0 = kNoBin; st->cnt0 = 0; st->krem0 = 0;
-            st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
+            st->lo = st->hi = k == 0 ? kKeyEnd : 0u;
+            st->sh1 = 0; st->exact = 1; st->krem0 = 0; st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
         }
         return;
     }
-    if (mine) {
+
+    // Rank band [lo_rank, hi_rank] (in counted elements, from the top) that holds the k-th element.
+    const bool exact = counted == n_s;
+    double lo_rank, hi_rank;
+    if (exact) {
+        lo_rank = (double)k - 1.0;   // bins with at most k-1 elements above them ...
+        hi_rank = (double)k;         // ... and at least k elements at or above them: one bin
+    } else {
+        const double frac = (double)k / (double)n_s;
+        const double ks = frac * (double)counted;
+        const double sd = sqrt(fmax(ks * (1.0 - frac), 1.0));
+        lo_rank = ks - kBandSigmas * sd - 2.0;
+        hi_rank = ks + kBandSigmas * sd + 2.0;
+    }
+    if (threadIdx.x == 0) { sh_hi = kDigit0Bins - 1; sh_lo = 0; sh_above_hi = 0; sh_in_range = 0; }
+    __syncthreads();
+    {
+        // b_hi = smallest bin with (#counted above it) <= lo_rank; b_lo = largest bin with
+        // (#counted at or above it) >= hi_rank.  Both conditions are monotone in the bin index.
+        uint32_t cgt = above, my_hi = 0xFFFFFFFFu, my_lo = 0;
+        bool any_lo = false;
+#pragma unroll
+        for (int j = 15; j >= 0; --j) {
+            const uint32_t bin = threadIdx.x * 16 + j;
+            if ((double)cgt <= lo_rank) my_hi = bin;                         // descending j: ends at the smallest
+            if (!any_lo && (double)(cgt + loc[j]) >= hi_rank) { my_lo = bin; any_lo = true; }   // first hit is the largest
+            cgt += loc[j];
+        }
+        if (my_hi != 0xFFFFFFFFu) atomicMin(&sh_hi, my_hi);
+        if (any_lo) atomicMax(&sh_lo, my_lo);
+    }
+    __syncthreads();
+    const uint32_t b_hi = sh_hi;
+    const uint32_t b_lo = min(sh_lo, b_hi);
+    {
+        uint32_t cgt = above, in_range = 0;
+#pragma unroll
+        for (int j = 15; j >= 0; --j) {
+            const uint32_t bin = threadIdx.x * 16 + j;
+            if (bin == b_hi) sh_above_hi = cgt;
+            if (bin >= b_lo && bin <= b_hi) in_range += loc[j];
+            cgt += loc[j];
+        }
+        if (in_range) atomicAdd(&sh_in_range, in_range);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
         st->cstar = 0;
         st->active = 1;
-        st->bin0 = bin; st->cnt0 = cnt; st->krem0 = krem;
+        st->lo = b_lo << kDigit0Shift;
+        st->hi = (b_hi + 1u) << kDigit0Shift;            // up to 2^31
+        st->sh1 = kDigit0Shift - kDigit1Bits + ceil_log2(b_hi - b_lo + 1u);
+        st->exact = exact ? 1u : 0u;
+        st->krem0 = exact ? k - sh_above_hi : 0u;
         st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
-        // The sum over scopes is at most n < 2^32, so the counter cannot wrap.
-        atomicAdd(&glob->cand_total, cnt);
+        // undecided elements this scope will produce (scaled up, with a margin, when sampled)
+        u64 est = sh_in_range;
+        if (!exact) est = (u64)((double)est * ((double)n_s / (double)counted) * 1.25) + 1024;
+        atomicAdd(&glob->cand_total, est);
     }
 }
 
-__global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(SegState* __restrict__ state,
-                                                                   uint32_t* __restrict__ hist1) {
+__global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(const SegDesc* __restrict__ seg,
+                                                                   SegState* __restrict__ state,
+                                                                   uint32_t* __restrict__ hist1,
+                                                                   const uint32_t* __restrict__ kept_above,
+                                                                   Globals* glob, uint32_t pass) {
     __shared__ uint32_t wave_sums[kDigit1Bins / 16 / 64];
+    __shared__ uint32_t sh_rank;
+    if (pass != 0 && !glob->retry) return;
     const uint32_t s = blockIdx.x;
     SegState* st = state + s;
-    const uint32_t k = st->active ? st->krem0 : 0u;
-    uint32_t bin = 0, krem = 0, cnt = 0;
-    const bool mine = select_bin<(int)kDigit1Bins>(hist1 + (size_t)s * kDigit1Bins, k, wave_sums, bin, krem, cnt);
-    if (mine) {
-        st->bin1 = bin; st->cnt1 = cnt; st->krem1 = krem;
+    const uint32_t active = st->active;
+    // Rank of the k-th element among the undecided ones.  Exact counts gave it before emit; a sampled
+    // bracket gets it from the number of elements emit found above the bracket, and is checked here.
+    if (threadIdx.x == 0) {
+        uint32_t rank = 0;
+        if (active) {
+            if (st->exact) {
+                rank = st->krem0;
+            } else {
+                uint32_t kept = 0;
+                for (uint32_t r = 0; r < kCandRegions; ++r)
+                    kept += kept_above[((size_t)s * kCandRegions + r) * kFillStride];
+                const uint32_t k = seg[s].k;
+                rank = k > kept ? k - kept : 0u;   // 0: more than k elements above the bracket
+            }
+        }
+        sh_rank = rank;
     }
+    __syncthreads();
+    const uint32_t rank = sh_rank;
+    uint32_t bin = 0, krem = 0, cnt = 0;
+    // (select_bin clears the histogram and finds nothing when rank is 0 or beyond the undecided count)
+    const bool mine = select_bin<(int)kDigit1Bins>(hist1 + (size_t)s * kDigit1Bins, rank, wave_sums, bin, krem, cnt);
+    if (threadIdx.x == 0) sh_rank = 0;
+    __syncthreads();
+    if (mine) {
+        st->krem0 = rank; st->bin1 = bin; st->cnt1 = cnt; st->krem1 = krem;
+        sh_rank = 1;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && active && sh_rank == 0) glob->retry = 1;   // the bracket missed the k-th element
 }
 
 // -------------------------------------------------------------------------------------- emit
-// Second pass over the weights.  With b0 the scope's digit-0 bin, lo = b0 << shift and
-// hi = (b0 + 1) << shift:   key >= hi -> kept;   lo <= key < hi -> undecided (candidate).
+// The pass over the weights that writes the mask.  With [lo, hi) the scope's bracket:
+// key >= hi -> kept;   lo <= key < hi -> undecided (candidate).
 //
 // Persistent workgroups of 4 waves walk 4096-element tiles, one 1024-element quarter per wave,
 // with streaming 16-byte loads.  A lane owns 4 consecutive elements, i.e. one nibble of a mask
@@ -265,7 +408,7 @@ constexpr uint32_t kEmitLoads = 4;                                  // 16-byte l
 constexpr uint32_t kEmitWaveTile = 64 * 4 * kEmitLoads;             // 1024 elements = 16 mask words
 constexpr uint32_t kEmitTile = kEmitWaves * kEmitWaveTile;          // 4096 elements
 constexpr uint32_t kStageCap = 1024;                                // staged composites per workgroup
-constexpr uint32_t kEmitRunLen = 4;                                 // tiles per run; staging is checked per run
+constexpr uint32_t kEmitRunLen = kRunLen;                           // tiles per run; staging is checked per run
 
 struct EmitShared {
     u64 stage[kStageCap];
@@ -273,6 +416,7 @@ struct EmitShared {
     uint32_t wave_sums[kEmitWaves];
     uint32_t stage_count;     // slots handed out (may exceed kStageCap: the excess went to global memory)
     uint32_t flush_base;
+    uint32_t kept;            // elements above the bracket seen by this workgroup in the current scope
 };
 
 __device__ __forceinline__ uint32_t or_over_8_lanes(uint32_t x) {
@@ -326,14 +470,22 @@ __device__ __forceinline__ void flush_stage(EmitShared& sh, Globals* glob, u64* 
     __syncthreads();
 }
 
-__device__ __forceinline__ void flush_hist1(uint32_t* lds_hist1, uint32_t* __restrict__ global_hist1) {
+// Adds the workgroup's digit-1 counts and its count of kept elements to the scope's totals.
+__device__ __forceinline__ void flush_scope(EmitShared& sh, uint32_t kept_in_lane, uint32_t* __restrict__ global_hist1,
+                                            uint32_t* __restrict__ kept_counter) {
+    const uint32_t wave_kept = wave_sum(kept_in_lane);
+    if (lane_id() == 0 && wave_kept) atomicAdd(&sh.kept, wave_kept);
     __syncthreads();
     for (uint32_t b = threadIdx.x; b < kDigit1Bins; b += kEmitBlock) {
-        const uint32_t v = lds_hist1[b];
+        const uint32_t v = sh.hist1[b];
         if (v) {
             atomicAdd(&global_hist1[b], v);
-            lds_hist1[b] = 0;
+            sh.hist1[b] = 0;
         }
+    }
+    if (threadIdx.x == 0) {
+        if (sh.kept) atomicAdd(kept_counter, sh.kept);
+        sh.kept = 0;
     }
     __syncthreads();
 }
@@ -342,29 +494,36 @@ template <bool VEC>
 __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restrict__ w, uint32_t n,
                                                           const SegDesc* __restrict__ seg, uint32_t nseg,
                                                           const SegState* __restrict__ state, Globals* glob,
-                                                          uint32_t* __restrict__ hist1, u64* __restrict__ cand,
-                                                          uint32_t cand_cap, u64* __restrict__ mask) {
+                                                          uint32_t* __restrict__ hist1,
+                                                          uint32_t* __restrict__ kept_above, u64* __restrict__ cand,
+                                                          uint32_t cand_cap, u64* __restrict__ mask, uint32_t pass) {
     __shared__ EmitShared sh;
+    if (pass != 0 && !glob->retry) return;             // the retry pass has nothing to do
     for (uint32_t j = threadIdx.x; j < kDigit1Bins; j += kEmitBlock) sh.hist1[j] = 0;
     for (uint32_t j = threadIdx.x; j < kStageCap; j += kEmitBlock) sh.stage[j] = 0;
-    if (threadIdx.x == 0) { sh.stage_count = 0; sh.flush_base = 0; }
+    if (threadIdx.x == 0) { sh.stage_count = 0; sh.flush_base = 0; sh.kept = 0; }
     __syncthreads();
 
     const uint32_t lane = lane_id();
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t region = blockIdx.x % kCandRegions;
     const uint32_t region_cap = cand_cap / kCandRegions;
-    // The number of undecided elements is known from the first pass; if they cannot fit, none is listed.
-    const bool listing = glob->cand_total <= cand_cap;
+    // The number of undecided elements is known (or estimated) from the histogram pass; if they cannot
+    // fit, none is listed.
+    const bool listing = glob->cand_total <= (u64)cand_cap;
     if (!listing && blockIdx.x == 0 && threadIdx.x == 0) glob->overflow = 1;
 
     const uint32_t num_tiles = (uint32_t)(((u64)n + kEmitTile - 1) / kEmitTile);
     const uint32_t kNone = 0xFFFFFFFFu;
     uint32_t cur = kNone;                        // scope whose digit-1 counts sit in LDS
-    uint32_t cur_begin = 0, cur_end = 0, s_lo = 0, s_hi = 0;
+    uint32_t cur_begin = 0, cur_end = 0, s_lo = 0, s_hi = 0, s_sh1 = 0;
+    uint32_t kept_in_lane = 0;                   // elements of scope `cur` above its bracket, this lane
+    auto kept_slot = [&](uint32_t scope) {
+        return kept_above + ((size_t)scope * kCandRegions + region) * kFillStride;
+    };
 
     for (uint32_t j = 0;; ++j) {
-        const uint32_t t = tile_of(j, kEmitRunLen);
+        const uint32_t t = tile_of(j);
         if (t >= num_tiles) break;
         const uint32_t a = t * kEmitTile;                               // < n
         const uint32_t b = (uint32_t)min((u64)a + kEmitTile, (u64)n);
@@ -390,13 +549,14 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
         const uint32_t s0_end = s0 == cur ? cur_end : seg[s0].end;
         const bool single = s0_end >= b;                                // whole tile inside one scope
         if (single && s0 != cur) {                                      // same decision in every wave
-            if (cur != kNone) flush_hist1(sh.hist1, hist1 + (size_t)cur * kDigit1Bins);
+            if (cur != kNone) flush_scope(sh, kept_in_lane, hist1 + (size_t)cur * kDigit1Bins, kept_slot(cur));
+            kept_in_lane = 0;
             cur = s0;
             cur_begin = seg[s0].begin;
             cur_end = s0_end;
-            const uint32_t bin0 = state[s0].bin0;
-            s_lo = bin0 << kDigit0Shift;
-            s_hi = (bin0 + 1u) << kDigit0Shift;
+            s_lo = state[s0].lo;
+            s_hi = state[s0].hi;
+            s_sh1 = state[s0].sh1;
         }
 
         if (single && whole) {
@@ -408,6 +568,7 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
                 const uint32_t k2 = key_of_bits(v[u].z), k3 = key_of_bits(v[u].w);
                 const uint32_t nib = (k0 >= s_hi ? 1u : 0u) | (k1 >= s_hi ? 2u : 0u) | (k2 >= s_hi ? 4u : 0u) |
                                      (k3 >= s_hi ? 8u : 0u);
+                kept_in_lane += (uint32_t)__popc(nib);
                 const uint32_t half = or_over_8_lanes(nib << ((lane & 7u) * 4u));
                 const u64 first = wave_first + u * 256u;                // first element of this wave step
                 if ((lane & 7u) == 0)
@@ -426,7 +587,7 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
                 const u32x4 q = (pick & 8u) ? ((pick & 4u) ? v[3] : v[2]) : ((pick & 4u) ? v[1] : v[0]);
                 const uint32_t raw = (pick & 2u) ? ((pick & 1u) ? q.w : q.z) : ((pick & 1u) ? q.y : q.x);
                 const uint32_t key = key_of_bits(raw);
-                if (has) atomicAdd(&sh.hist1[digit1_of(key)], 1u);
+                if (has) atomicAdd(&sh.hist1[(key - s_lo) >> s_sh1], 1u);
                 if (listing) {
                     const uint32_t count = (uint32_t)__popcll(cm);
                     const uint32_t i = (uint32_t)wave_first + (pick >> 2) * 256u + lane * 4u + (pick & 3u);
@@ -458,11 +619,12 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
                         const uint32_t i = (uint32_t)i64;
                         const uint32_t key = key_of_bits(__float_as_uint(w[i]));
                         const uint32_t si = find_seg(seg, nseg, i);
-                        const uint32_t bin0 = state[si].bin0;
-                        const uint32_t d0 = digit0_of(key);
-                        if (d0 > bin0) nib |= 1u << e;
-                        if (d0 == bin0) {
-                            atomicAdd(&hist1[(size_t)si * kDigit1Bins + digit1_of(key)], 1u);
+                        const uint32_t lo = state[si].lo, hi = state[si].hi;
+                        if (key >= hi) {
+                            nib |= 1u << e;
+                            if (!state[si].exact) atomicAdd(kept_slot(si), 1u);
+                        } else if (key >= lo) {
+                            atomicAdd(&hist1[(size_t)si * kDigit1Bins + ((key - lo) >> state[si].sh1)], 1u);
                             if (listing) {
                                 const uint32_t g = reserve_region(glob, region, 1u, region_cap);
                                 if (g != kNoSlot) cand[(size_t)region * region_cap + g] = composite_of(key, i);
@@ -478,7 +640,7 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
         }
     }
     if (listing) flush_stage(sh, glob, cand, region, region_cap);
-    if (cur != kNone) flush_hist1(sh.hist1, hist1 + (size_t)cur * kDigit1Bins);
+    if (cur != kNone) flush_scope(sh, kept_in_lane, hist1 + (size_t)cur * kDigit1Bins, kept_slot(cur));
 }
 
 // ----------------------------------------------------------------------------------- compact2
@@ -506,7 +668,7 @@ __global__ __launch_bounds__(kListBlock) void compact2_kernel(const SegDesc* __r
         for (u64 j = (u64)blockIdx.x * kListBlock + threadIdx.x; j < fill; j += (u64)gridDim.x * kListBlock) {
             const u64 c = src[j];
             const uint32_t s = nseg > 1 ? find_seg(seg, nseg, index_of(c)) : 0u;
-            if (digit1_of((uint32_t)(c >> 32)) == state[s].bin1) {
+            if ((((uint32_t)(c >> 32) - state[s].lo) >> state[s].sh1) == state[s].bin1) {
                 const uint32_t pos = atomicAdd(&nfound, 1u);
                 if (pos < kMatchSlotsPerBlock) found[pos] = c;
             }
@@ -521,7 +683,7 @@ __global__ __launch_bounds__(kListBlock) void compact2_kernel(const SegDesc* __r
 }
 
 // -------------------------------------------------------------------------------------- final
-// Resolves the low kTailBits bits of C* for one scope.  The source is the scope's matches, gathered
+// Resolves the bits of C* below digit 1 for one scope.  The source is the scope's matches, gathered
 // from the match slots into LDS (every one agrees with C* on digits 0 and 1), or, when the lists
 // are not usable, the scope's weights filtered on the fly.
 constexpr int kFinalBlock = 1024;
@@ -530,10 +692,10 @@ constexpr uint32_t kFinalList = 4096;   // matches of one scope that fit in LDS
 template <bool FROM_LIST>
 __device__ __forceinline__ void final_levels(const u64* list, uint32_t list_cnt,
                                              const float* __restrict__ w, uint32_t begin, uint32_t end,
-                                             u64& prefix, uint32_t& krem, uint32_t* hist, uint32_t* wave_sums,
-                                             uint32_t* found) {
+                                             uint32_t tail_bits, u64& prefix, uint32_t& krem, uint32_t* hist,
+                                             uint32_t* wave_sums, uint32_t* found) {
     // 8-bit digits over the tail bits, most significant first; the last digit takes what is left
-    uint32_t resolved_above = kTailBits;   // bits >= this position are already fixed in `prefix`
+    uint32_t resolved_above = tail_bits;   // bits >= this position are already fixed in `prefix`
     while (resolved_above > 0) {
         const uint32_t width = resolved_above >= 8 ? 8u : resolved_above;
         const uint32_t shift = resolved_above - width;
@@ -582,7 +744,10 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
     const uint32_t s = blockIdx.x;
     SegState* st = state + s;
     if (!st->active) return;
-    u64 prefix = ((u64)st->bin0 << (32 + kDigit0Shift)) | ((u64)st->bin1 << (32 + kDigit1Shift));
+    // Every key in digit-1 bin b1 lies in [lo + (b1 << sh1), lo + ((b1 + 1) << sh1)), a range aligned
+    // to 2^sh1, so the composites there share all bits from 32 + sh1 up.
+    const uint32_t tail_bits = 32u + st->sh1;
+    u64 prefix = (u64)(st->lo + (st->bin1 << st->sh1)) << 32;
     uint32_t krem = st->krem1;
     const uint32_t begin = seg[s].begin, end = seg[s].end;
     const uint32_t cnt1 = st->cnt1;
@@ -603,9 +768,9 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
         }
         __syncthreads();
         const uint32_t count = min(gathered, kFinalList);
-        final_levels<true>(list, count, nullptr, 0, 0, prefix, krem, hist, wave_sums, found);
+        final_levels<true>(list, count, nullptr, 0, 0, tail_bits, prefix, krem, hist, wave_sums, found);
     } else {
-        final_levels<false>(nullptr, 0, w, begin, end, prefix, krem, hist, wave_sums, found);
+        final_levels<false>(nullptr, 0, w, begin, end, tail_bits, prefix, krem, hist, wave_sums, found);
     }
     if (threadIdx.x == 0) st->cstar = prefix;
 }
@@ -638,18 +803,19 @@ __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restri
         const u64 tid = ((u64)blockIdx.y * gridDim.x + blockIdx.x) * kListBlock + threadIdx.x;
         const u64 nthreads = (u64)gridDim.x * gridDim.y * kListBlock;
         const uint32_t kNone = 0xFFFFFFFFu;
-        uint32_t s = kNone, s_begin = 0, s_end = 0, bin0 = 0;
+        uint32_t s = kNone, s_begin = 0, s_end = 0, lo = 0, hi = 0;
         u64 cstar = 0;
         for (u64 i = tid; i < n; i += nthreads) {
             if (s == kNone || i < s_begin || i >= s_end) {
                 s = find_seg(seg, nseg, (uint32_t)i);
                 s_begin = seg[s].begin;
                 s_end = seg[s].end;
-                bin0 = state[s].bin0;
+                lo = state[s].lo;
+                hi = state[s].hi;
                 cstar = state[s].cstar;
             }
             const uint32_t key = key_of_bits(__float_as_uint(w[i]));
-            if (digit0_of(key) == bin0 && composite_of(key, (uint32_t)i) >= cstar)
+            if (key >= lo && key < hi && composite_of(key, (uint32_t)i) >= cstar)
                 atomicOr(&mask[i >> 6], 1ull << (i & 63u));
         }
     }
@@ -677,12 +843,6 @@ __device__ __forceinline__ u64 tile_load(const u64* p) {
 }
 __device__ __forceinline__ void tile_store(u64* p, u64 v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-    return v;
 }
 
 // Inclusive prefix sum over the 64 lanes of a wave.
@@ -806,37 +966,45 @@ uint32_t resident_blocks(K kernel, int block, int num_cu, uint32_t fallback_per_
 }  // namespace
 
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
-                             unsigned long long* d_mask, uint32_t* d_prefix, int num_cu, hipStream_t stream) {
+                             uint64_t sampled_elems, unsigned long long* d_mask, uint32_t* d_prefix, int num_cu,
+                             hipStream_t stream) {
     if (n == 0) return hipSuccess;
     const uint32_t words = div_up_u64(n, 64);
     const bool aligned = (reinterpret_cast<uintptr_t>(d_weights) & 15u) == 0;
 
-    {
-        const uint32_t num_tiles = div_up_u64(n, kHistTile);
-        static const uint32_t want = resident_blocks(hist0_kernel<true>, kHistBlock, num_cu, 2);
-        const uint32_t grid = num_tiles < want ? num_tiles : want;
-        const uint32_t run_len = 4;
+    static const uint32_t hist_want = resident_blocks(hist0_kernel<true>, kHistBlock, num_cu, 2);
+    static const uint32_t emit_want = resident_blocks(emit_kernel<true>, kEmitBlock, num_cu, 4);
+    const uint32_t hist_tiles = div_up_u64(n, kHistTile), emit_tiles = div_up_u64(n, kEmitTile);
+    const uint32_t hist_grid = hist_tiles < hist_want ? hist_tiles : hist_want;
+    const uint32_t emit_grid = emit_tiles < emit_want ? emit_tiles : emit_want;
+    // Pass 0 works from (possibly sampled) histograms; pass 1 repeats the four kernels with full
+    // counts if a sampled bracket missed, and returns at once otherwise.
+    for (uint32_t pass = 0; pass < 2; ++pass) {
+        // The sampled pass visits few tiles: no more workgroups than tiles.
+        uint32_t grid = hist_grid;
+        if (pass == 0) {
+            const uint32_t visited = div_up_u64(sampled_elems, kHistTile);
+            if (visited < grid) grid = visited < 1 ? 1 : visited;
+        }
         if (aligned)
-            hipLaunchKernelGGL((hist0_kernel<true>), dim3(grid), dim3(kHistBlock), 0, stream, d_weights, n, s.seg,
-                               nseg, s.hist0, s.glob, run_len);
+            hipLaunchKernelGGL((hist0_kernel<true>), dim3(grid), dim3(kHistBlock), 0, stream, d_weights, n,
+                               s.seg, nseg, s.hist0, s.glob, pass);
         else
-            hipLaunchKernelGGL((hist0_kernel<false>), dim3(grid), dim3(kHistBlock), 0, stream, d_weights, n, s.seg,
-                               nseg, s.hist0, s.glob, run_len);
-    }
-    hipLaunchKernelGGL(select0_kernel, dim3(nseg), dim3(kDigit0Bins / 16), 0, stream, s.seg, s.state, s.hist0,
-                       s.glob);
-    {
-        const uint32_t num_tiles = div_up_u64(n, kEmitTile);
-        static const uint32_t want = resident_blocks(emit_kernel<true>, kEmitBlock, num_cu, 4);
-        const uint32_t grid = num_tiles < want ? num_tiles : want;
+            hipLaunchKernelGGL((hist0_kernel<false>), dim3(grid), dim3(kHistBlock), 0, stream, d_weights, n,
+                               s.seg, nseg, s.hist0, s.glob, pass);
+        hipLaunchKernelGGL(select0_kernel, dim3(nseg), dim3(kDigit0Bins / 16), 0, stream, s.seg, s.state, s.hist0,
+                           s.kept_above, s.glob, pass);
         if (aligned)
-            hipLaunchKernelGGL((emit_kernel<true>), dim3(grid), dim3(kEmitBlock), 0, stream, d_weights, n, s.seg,
-                               nseg, s.state, s.glob, s.hist1, s.cand, s.cand_cap, d_mask);
+            hipLaunchKernelGGL((emit_kernel<true>), dim3(emit_grid), dim3(kEmitBlock), 0, stream, d_weights, n,
+                               s.seg, nseg, s.state, s.glob, s.hist1, s.kept_above, s.cand, s.cand_cap, d_mask,
+                               pass);
         else
-            hipLaunchKernelGGL((emit_kernel<false>), dim3(grid), dim3(kEmitBlock), 0, stream, d_weights, n, s.seg,
-                               nseg, s.state, s.glob, s.hist1, s.cand, s.cand_cap, d_mask);
+            hipLaunchKernelGGL((emit_kernel<false>), dim3(emit_grid), dim3(kEmitBlock), 0, stream, d_weights, n,
+                               s.seg, nseg, s.state, s.glob, s.hist1, s.kept_above, s.cand, s.cand_cap, d_mask,
+                               pass);
+        hipLaunchKernelGGL(select1_kernel, dim3(nseg), dim3(kDigit1Bins / 16), 0, stream, s.seg, s.state, s.hist1,
+                           s.kept_above, s.glob, pass);
     }
-    hipLaunchKernelGGL(select1_kernel, dim3(nseg), dim3(kDigit1Bins / 16), 0, stream, s.state, s.hist1);
 
     const uint32_t list_blocks = 256;   // per candidate region
     static_assert(kListBlock == 256, "compact2 runs 4 waves per workgroup");

@@ -142,6 +142,31 @@ def test_build_mask_in_place_selection_when_candidates_do_not_fit(pac):
         c.close()
 
 
+@pytest.mark.parametrize("kind", ["gauss", "ties", "zeros_half"])
+def test_build_mask_large_scope_sampled_histogram(ctx, kind):
+    """Scopes above 8M elements get their bracket from a sampled histogram; the mask is exact all the same."""
+    rng = np.random.default_rng(51)
+    n = 20_000_003
+    w = weights_of(kind, n, rng)
+    for s in (0.5, 0.9):
+        check_mask(ctx, w, [0, n], s, f"sampled {kind} s={s}")
+    check_mask(ctx, w, [0, 1000, 9_000_000, n], [0.5, 0.9, 0.7], f"sampled segmented {kind}")
+
+
+def test_build_mask_sampled_bracket_miss_falls_back_to_full_counts(ctx):
+    """Tile-constant magnitudes make a tile sample a poor predictor of the quantile: the sampled bracket
+    misses, the call repeats the selection with full counts, and the result is still the oracle's."""
+    rng = np.random.default_rng(52)
+    tile = 16384
+    tiles = 1300
+    n = tiles * tile + 77
+    per_tile = (rng.random(tiles + 1) * 4.0 + 0.01).astype(np.float32)
+    w = np.repeat(per_tile, tile)[:n].copy()
+    w[::3] *= -1.0
+    for s in (0.3, 0.5, 0.77):
+        check_mask(ctx, w, [0, n], s, f"tile-constant s={s}")
+
+
 def test_build_mask_is_deterministic(ctx):
     rng = np.random.default_rng(24)
     n = (1 << 21) + 13
