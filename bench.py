@@ -21,6 +21,18 @@ if ROOT not in sys.path:
 
 METRIC = "dense-gradient GB/s through mask+compress+sum+decompress; % of HBM peak"
 HBM_PEAK_GBPS = 8000.0
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "compress_c4_hbm_traffic.txt")
+
+
+def measured_traffic(config_id: int):
+    """HBM bytes per pac_compress launch from the committed rocprofv3 counter summary (None if absent or
+    for another workload)."""
+    if config_id != 4 or not os.path.exists(TRAFFIC_SUMMARY):
+        return None
+    for line in open(TRAFFIC_SUMMARY):
+        if line.startswith("traffic_bytes_per_launch"):
+            return int(float(line.split("=")[1].split()[0]))
+    return None
 
 
 def parse_args():
@@ -31,6 +43,9 @@ def parse_args():
     ap.add_argument("--config", type=int, default=4, help="workload id 1..5 (4 = the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=1 << 28)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy before the timed loop: a kernel of known traffic "
+                         "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     return ap.parse_args()
 
 
@@ -137,6 +152,13 @@ def main() -> int:
         pac.pac_decompress(h, red, mask, prefix, dense_out, nnz)
         return nnz
 
+    if args.pmc_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     for t in range(args.warmup):
         step(t, False)
     torch.cuda.synchronize()
@@ -203,7 +225,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "traffic": measured_traffic(args.config),
             "bytes_per_launch": alg["compress"],
             "avg_launch_ms": round(compress_ms, 5),
         },
