@@ -1,0 +1,81 @@
+"""GPU parity at the full sizes of the measured configurations, in the launch configuration bench.py
+times (same context sizing, same calls, inputs generated on the device and copied to the host for
+the oracle).  The oracle is fast enough to check every output element at these sizes, so nothing is
+sampled except that the largest configuration runs with 2 of its 8 workers to bound host memory.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import make_workload
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def raw_np(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.float32:
+        return t.cpu().numpy().view(np.uint32)
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def run_full(config_id: int, workers=None, steps=(0,)):
+    import paper_2505_18563_amd as pac
+    assert torch.cuda.is_available()
+    dev = torch.device("cuda", 0)
+    wl = make_workload(config_id, device=dev, workers=workers)
+    n, W = wl.n, wl.workers
+    code = oracle.F32 if wl.dtype == "f32" else oracle.BF16
+    nseg = len(wl.scope_offsets) - 1
+    print(f"[full] C{config_id} {wl.name} n={n} W={W} nseg={nseg} dtype={wl.dtype}", flush=True)
+    w_np = wl.weights.cpu().numpy()
+    g_np = [raw_np(g) for g in wl.grads]
+    if code == oracle.F32:
+        g_np = [g.view(np.float32) for g in g_np]
+    ctx = pac.PacContext(max_elems=n, max_segments=nseg, device=0)
+    try:
+        for step in steps:
+            sp = wl.sparsity_at(step)
+            print(f"[full]   step {step} s={sp[0]}: GPU", flush=True)
+            mask, prefix, nnz = ctx.build_mask(wl.weights, wl.scope_offsets, sp)
+            compact = [ctx.compress(g, mask, prefix, nnz) for g in wl.grads]
+            red = ctx.reduce_local(compact, nnz)
+            out = ctx.decompress(red, mask, prefix, n, nnz)
+            torch.cuda.synchronize()
+
+            print(f"[full]   step {step}: oracle mask", flush=True)
+            em, ep, k = oracle.build_mask(w_np, wl.scope_offsets, sp)
+            assert nnz == k
+            assert np.array_equal(mask.cpu().numpy().view(np.uint64), em), "mask words differ"
+            assert np.array_equal(prefix.cpu().numpy().view(np.uint32), ep), "prefix differs"
+            print(f"[full]   step {step}: oracle compress x{W}", flush=True)
+            e_compact = []
+            for w in range(W):
+                ec = oracle.compress(g_np[w], em, k, code)
+                assert np.array_equal(raw_np(compact[w]), ec.view(raw_np(compact[w]).dtype)), f"compact[{w}] differs"
+                e_compact.append(ec)
+            print(f"[full]   step {step}: oracle sum + decompress", flush=True)
+            e_red = oracle.reduce_local(e_compact, code)
+            got_red = raw_np(red)
+            assert np.array_equal(got_red, e_red.view(got_red.dtype)), "reduced buffer differs"
+            del e_compact
+            e_out = oracle.decompress(e_red, em, n, code)
+            got_out = raw_np(out)
+            assert np.array_equal(got_out, e_out.view(got_out.dtype)), "dense output differs"
+            del e_out, got_out, compact, red, out
+    finally:
+        ctx.close()
+
+
+def test_full_config3_bert_base_shaped_global_prune():
+    run_full(3)
+
+
+def test_full_config4_gpt2_medium_shaped_bf16_w16():
+    """The benchmark workload: 354,823,168 elements, one prune scope (sampled bracket), 16 bf16 workers."""
+    run_full(4)
+
+
+def test_full_config5_decoder_1p3b_per_layer_schedule_two_workers():
+    """1,315,723,264 elements, 292 prune scopes (the large ones sampled), every sparsity of the schedule."""
+    run_full(5, workers=2, steps=(0, 1, 2))
