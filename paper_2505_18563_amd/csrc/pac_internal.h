@@ -43,8 +43,14 @@ struct SegState {
     uint32_t bin1;             // digit 1 of the k-th element
     uint32_t cnt1;             // undecided elements with that digit
     uint32_t krem1;            // rank of the k-th element among those
-    uint32_t pad[3];
+    uint32_t in_place;         // small scope: its undecided elements are not listed, `final` and `fixup`
+                               // walk its weights (cheap, and keeps all-tie vectors out of the lists)
+    uint32_t heavy;            // too many undecided elements share digit 1 for `final`'s LDS list:
+                               // `final` walks this scope's weights
+    uint32_t pad;
 };
+
+constexpr uint32_t kSmallScope = 65536;   // scopes up to this many elements are resolved in place
 
 // The candidate list is split into regions with one fill counter each: an atomic on one address
 // costs about 10 ns and is serialised, so the appends of a call are spread over several addresses

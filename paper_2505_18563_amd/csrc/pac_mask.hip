@@ -61,6 +61,22 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
     return v;
 }
 
+// atomicAdd(base + idx, 1) for every lane with `active`.  Equal magnitudes (all-zero biases, unit
+// norm scales) put whole waves on one counter, and atomics on one address are serialised: when all
+// active lanes agree on idx the wave issues a single atomic with their number; otherwise the lanes
+// mostly differ and each issues its own.  Must be called by all lanes of the wave.
+__device__ __forceinline__ void wave_aggregated_inc(uint32_t* __restrict__ base, uint32_t idx, bool active) {
+    const u64 todo = __ballot(active);
+    if (todo == 0) return;
+    const uint32_t leader = (uint32_t)__ffsll((long long)todo) - 1u;
+    const uint32_t lead_idx = (uint32_t)__shfl((int)idx, (int)leader, 64);
+    if (__ballot(active && idx == lead_idx) == todo) {
+        if (lane_id() == leader) atomicAdd(base + lead_idx, (uint32_t)__popcll(todo));
+    } else if (active) {
+        atomicAdd(base + idx, 1u);
+    }
+}
+
 // First scope whose end exceeds flat index i (scopes ascending; empty scopes are never returned).
 // Requires i < seg[nseg-1].end.
 __device__ __forceinline__ uint32_t find_seg(const SegDesc* __restrict__ seg, uint32_t nseg, uint32_t i) {
@@ -180,10 +196,16 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
         } else {
             // The tile crosses scope boundaries: element by element into the global histograms,
             // each element under its own scope's sampling rule.
-            for (u64 i = (u64)a + threadIdx.x; i < b; i += kHistBlock) {
-                const uint32_t si = find_seg(seg, nseg, (uint32_t)i);
-                if (pass != 0 || tile_sampled(t, seg[si].stride))
-                    atomicAdd(&hist0[(size_t)si * kDigit0Bins + digit0_of(key_of_bits(__float_as_uint(w[i])))], 1u);
+            for (u64 i0 = a; i0 < b; i0 += kHistBlock) {   // same trip count in every lane
+                const u64 i = i0 + threadIdx.x;
+                bool count = i < b;
+                uint32_t idx = 0;
+                if (count) {
+                    const uint32_t si = find_seg(seg, nseg, (uint32_t)i);
+                    count = pass != 0 || tile_sampled(t, seg[si].stride);
+                    idx = si * kDigit0Bins + digit0_of(key_of_bits(__float_as_uint(w[i])));
+                }
+                wave_aggregated_inc(hist0, idx, count);
             }
         }
     }
@@ -231,6 +253,8 @@ __device__ __forceinline__ bool select_bin(uint32_t* __restrict__ h, uint32_t k,
     }
     return mine;
 }
+
+constexpr uint32_t kFinalList = 4096;   // matches of one scope that `final` can hold in LDS
 
 __device__ __forceinline__ uint32_t ceil_log2(uint32_t x) { return x <= 1 ? 0u : 32u - (uint32_t)__clz((int)(x - 1)); }
 
@@ -280,6 +304,7 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
             st->active = 0;
             st->lo = st->hi = k == 0 ? kKeyEnd : 0u;
             st->sh1 = 0; st->exact = 1; st->krem0 = 0; st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
+            st->in_place = 1; st->heavy = 0;
         }
         return;
     }
@@ -338,10 +363,12 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
         st->exact = exact ? 1u : 0u;
         st->krem0 = exact ? k - sh_above_hi : 0u;
         st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
-        // undecided elements this scope will produce (scaled up, with a margin, when sampled)
+        st->in_place = n_s <= kSmallScope ? 1u : 0u;
+        st->heavy = 0;
+        // undecided elements this scope will list (scaled up, with a margin, when sampled)
         u64 est = sh_in_range;
         if (!exact) est = (u64)((double)est * ((double)n_s / (double)counted) * 1.25) + 1024;
-        atomicAdd(&glob->cand_total, est);
+        if (n_s > kSmallScope) atomicAdd(&glob->cand_total, est);
     }
 }
 
@@ -382,6 +409,7 @@ __global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(const SegDesc
     __syncthreads();
     if (mine) {
         st->krem0 = rank; st->bin1 = bin; st->cnt1 = cnt; st->krem1 = krem;
+        st->heavy = cnt > kFinalList ? 1u : 0u;
         sh_rank = 1;
     }
     __syncthreads();
@@ -517,6 +545,7 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
     const uint32_t kNone = 0xFFFFFFFFu;
     uint32_t cur = kNone;                        // scope whose digit-1 counts sit in LDS
     uint32_t cur_begin = 0, cur_end = 0, s_lo = 0, s_hi = 0, s_sh1 = 0;
+    bool s_list = false;                         // undecided elements of scope `cur` go to the candidate list
     uint32_t kept_in_lane = 0;                   // elements of scope `cur` above its bracket, this lane
     auto kept_slot = [&](uint32_t scope) {
         return kept_above + ((size_t)scope * kCandRegions + region) * kFillStride;
@@ -557,6 +586,7 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
             s_lo = state[s0].lo;
             s_hi = state[s0].hi;
             s_sh1 = state[s0].sh1;
+            s_list = listing && !state[s0].in_place;
         }
 
         if (single && whole) {
@@ -588,7 +618,7 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
                 const uint32_t raw = (pick & 2u) ? ((pick & 1u) ? q.w : q.z) : ((pick & 1u) ? q.y : q.x);
                 const uint32_t key = key_of_bits(raw);
                 if (has) atomicAdd(&sh.hist1[(key - s_lo) >> s_sh1], 1u);
-                if (listing) {
+                if (s_list) {
                     const uint32_t count = (uint32_t)__popcll(cm);
                     const uint32_t i = (uint32_t)wave_first + (pick >> 2) * 256u + lane * 4u + (pick & 3u);
                     uint32_t base = 0;
@@ -607,7 +637,8 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
                 }
             }
         } else {
-            // Plain path: every lane handles 4 consecutive elements with its own bounds and scope lookups.
+            // Plain path: every lane handles 4 consecutive elements with its own bounds and scope lookups;
+            // counters are bumped once per wave and distinct target.
 #pragma unroll 1
             for (uint32_t u = 0; u < kEmitLoads; ++u) {
                 const u64 first = wave_first + u * 256u;
@@ -615,21 +646,29 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
 #pragma unroll 1
                 for (uint32_t e = 0; e < 4; ++e) {
                     const u64 i64 = first + lane * 4u + e;
+                    const uint32_t i = (uint32_t)i64;
+                    bool kept = false, undecided = false, append = false;
+                    uint32_t key = 0, si = 0, d1 = 0;
                     if (i64 < n) {
-                        const uint32_t i = (uint32_t)i64;
-                        const uint32_t key = key_of_bits(__float_as_uint(w[i]));
-                        const uint32_t si = find_seg(seg, nseg, i);
+                        key = key_of_bits(__float_as_uint(w[i]));
+                        si = find_seg(seg, nseg, i);
                         const uint32_t lo = state[si].lo, hi = state[si].hi;
-                        if (key >= hi) {
-                            nib |= 1u << e;
-                            if (!state[si].exact) atomicAdd(kept_slot(si), 1u);
-                        } else if (key >= lo) {
-                            atomicAdd(&hist1[(size_t)si * kDigit1Bins + ((key - lo) >> state[si].sh1)], 1u);
-                            if (listing) {
-                                const uint32_t g = reserve_region(glob, region, 1u, region_cap);
-                                if (g != kNoSlot) cand[(size_t)region * region_cap + g] = composite_of(key, i);
-                            }
-                        }
+                        kept = key >= hi;
+                        undecided = !kept && key >= lo;
+                        if (undecided) d1 = (key - lo) >> state[si].sh1;
+                        append = undecided && listing && !state[si].in_place;
+                        if (kept) nib |= 1u << e;
+                        kept = kept && !state[si].exact;   // only sampled scopes need the count
+                    }
+                    wave_aggregated_inc(kept_above, (si * kCandRegions + region) * kFillStride, kept);
+                    wave_aggregated_inc(hist1, si * kDigit1Bins + d1, undecided);
+                    const u64 am = __ballot(append);
+                    if (am != 0) {
+                        uint32_t g = 0;
+                        if (lane == 0) g = reserve_region(glob, region, (uint32_t)__popcll(am), region_cap);
+                        g = __builtin_amdgcn_readfirstlane(g);
+                        if (append && g != kNoSlot)
+                            cand[(size_t)region * region_cap + g + lanes_below(am)] = composite_of(key, i);
                     }
                 }
                 const uint32_t half = or_over_8_lanes(nib << ((lane & 7u) * 4u));
@@ -668,7 +707,7 @@ __global__ __launch_bounds__(kListBlock) void compact2_kernel(const SegDesc* __r
         for (u64 j = (u64)blockIdx.x * kListBlock + threadIdx.x; j < fill; j += (u64)gridDim.x * kListBlock) {
             const u64 c = src[j];
             const uint32_t s = nseg > 1 ? find_seg(seg, nseg, index_of(c)) : 0u;
-            if ((((uint32_t)(c >> 32) - state[s].lo) >> state[s].sh1) == state[s].bin1) {
+            if (!state[s].heavy && (((uint32_t)(c >> 32) - state[s].lo) >> state[s].sh1) == state[s].bin1) {
                 const uint32_t pos = atomicAdd(&nfound, 1u);
                 if (pos < kMatchSlotsPerBlock) found[pos] = c;
             }
@@ -687,7 +726,6 @@ __global__ __launch_bounds__(kListBlock) void compact2_kernel(const SegDesc* __r
 // from the match slots into LDS (every one agrees with C* on digits 0 and 1), or, when the lists
 // are not usable, the scope's weights filtered on the fly.
 constexpr int kFinalBlock = 1024;
-constexpr uint32_t kFinalList = 4096;   // matches of one scope that fit in LDS
 
 template <bool FROM_LIST>
 __device__ __forceinline__ void final_levels(const u64* list, uint32_t list_cnt,
@@ -753,7 +791,7 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
     const uint32_t cnt1 = st->cnt1;
     if (threadIdx.x == 0) { found[0] = 0; found[1] = 0; gathered = 0; }
     __syncthreads();
-    const bool from_list = !glob->overflow && !glob->match_overflow && cnt1 <= kFinalList;
+    const bool from_list = !glob->overflow && !glob->match_overflow && !st->in_place && !st->heavy;
     if (from_list) {
         // Matches of this scope: thread t looks through the slots of compact2's workgroup t.
         static_assert(kFinalBlock == (int)kMatchBlocks, "one thread per compact2 workgroup");
@@ -797,6 +835,18 @@ __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restri
             const uint32_t i = index_of(c);
             const uint32_t s = nseg > 1 ? find_seg(seg, nseg, i) : 0u;
             if (c >= state[s].cstar) atomicOr(&mask[i >> 6], 1ull << (i & 63u));
+        }
+        // Scopes resolved in place have no list entries: walk their weights, one workgroup per scope.
+        for (uint32_t s = blockIdx.y * gridDim.x + blockIdx.x; s < nseg; s += gridDim.x * gridDim.y) {
+            const SegState* st = state + s;
+            if (!st->active || !st->in_place) continue;
+            const uint32_t lo = st->lo, hi = st->hi;
+            const u64 cstar = st->cstar;
+            for (u64 i = (u64)seg[s].begin + threadIdx.x; i < seg[s].end; i += kListBlock) {
+                const uint32_t key = key_of_bits(__float_as_uint(w[i]));
+                if (key >= lo && key < hi && composite_of(key, (uint32_t)i) >= cstar)
+                    atomicOr(&mask[i >> 6], 1ull << (i & 63u));
+            }
         }
     } else {
         // Lists not in use: walk the weights.
