@@ -73,7 +73,7 @@ uint32_t elem_size(pac_dtype dt) { return dt == PAC_F32 ? 4u : 2u; }
 // in full; larger ones keep at least about 4M sampled elements, at most one 16384-element tile in 16.
 uint32_t sample_stride(uint64_t len) {
     uint32_t stride = 1;
-    while (stride < 16 && len / (2ull * stride) >= (1ull << 22)) stride *= 2;
+    while (stride < pac::kMaxSampleStride && len / (2ull * stride) >= (1ull << 22)) stride *= 2;
     return stride;
 }
 

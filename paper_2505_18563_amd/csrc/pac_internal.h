@@ -50,6 +50,8 @@ struct SegState {
     uint32_t pad;
 };
 
+constexpr uint32_t kMaxSampleStride = 16;  // largest SegDesc::stride (power of two)
+
 constexpr uint32_t kSmallScope = 65536;   // scopes up to this many elements are resolved in place
 
 // The candidate list is split into regions with one fill counter each: an atomic on one address

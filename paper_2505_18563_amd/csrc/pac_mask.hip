@@ -159,9 +159,12 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
     uint32_t cur = kNone;   // scope whose counts sit in the LDS histogram
     uint32_t cur_begin = 0, cur_end = 0, cur_stride = 1;
 
-    for (uint32_t j = 0;; ++j) {
-        const uint32_t t = tile_of(j);
-        if (t >= num_tiles) break;
+    // Each workgroup owns one contiguous range of tiles, so it meets few scope boundaries and
+    // flushes its histogram rarely.
+    const uint32_t per_block = (num_tiles + gridDim.x - 1) / gridDim.x;
+    const uint32_t t_begin = blockIdx.x * per_block;
+    const uint32_t t_end = min(num_tiles, t_begin + per_block);
+    for (uint32_t t = t_begin; t < t_end; ++t) {
         const uint32_t a = t * kHistTile;
         const uint32_t b = (uint32_t)min((u64)a + kHistTile, (u64)n);
         uint32_t s = cur;
