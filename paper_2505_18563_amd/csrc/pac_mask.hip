@@ -522,7 +522,10 @@ __device__ __forceinline__ void flush_scope(EmitShared& sh, uint32_t kept_in_lan
 }
 
 template <bool VEC>
-__global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restrict__ w, uint32_t n,
+#ifndef PAC_EXP_EMIT_WAVES
+#define PAC_EXP_EMIT_WAVES 1
+#endif
+__global__ __launch_bounds__(kEmitBlock, PAC_EXP_EMIT_WAVES) void emit_kernel(const float* __restrict__ w, uint32_t n,
                                                           const SegDesc* __restrict__ seg, uint32_t nseg,
                                                           const SegState* __restrict__ state, Globals* glob,
                                                           uint32_t* __restrict__ hist1,
@@ -604,8 +607,13 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const float* __restric
                 kept_in_lane += (uint32_t)__popc(nib);
                 const uint32_t half = or_over_8_lanes(nib << ((lane & 7u) * 4u));
                 const u64 first = wave_first + u * 256u;                // first element of this wave step
+#ifdef PAC_EXP_EMIT_NT
+                if ((lane & 7u) == 0)
+                    __builtin_nontemporal_store(half, reinterpret_cast<uint32_t*>(mask) + (first >> 5) + (lane >> 3));
+#else
                 if ((lane & 7u) == 0)
                     reinterpret_cast<uint32_t*>(mask)[(first >> 5) + (lane >> 3)] = half;
+#endif
                 const uint32_t und = (k0 - s_lo < width ? 1u : 0u) | (k1 - s_lo < width ? 2u : 0u) |
                                      (k2 - s_lo < width ? 4u : 0u) | (k3 - s_lo < width ? 8u : 0u);
                 und_bits |= und << (4u * u);
