@@ -49,6 +49,12 @@ def _load():
         lib.orc_decompress.argtypes = [vp, i32, u64, vp, vp, u64]
         lib.orc_f32_to_bf16.restype = None
         lib.orc_f32_to_bf16.argtypes = [vp, vp, u64]
+        lib.orc_mask_from_nonzero.restype = u64
+        lib.orc_mask_from_nonzero.argtypes = [vp, i32, u64, vp, vp]
+        lib.orc_mask_diff.restype = u64
+        lib.orc_mask_diff.argtypes = [vp, vp, u64]
+        lib.orc_decompress_update.restype = u64
+        lib.orc_decompress_update.argtypes = [vp, i32, u64, vp, ctypes.c_float, vp, u64]
         _lib = lib
     return _lib
 
@@ -122,3 +128,59 @@ def f32_to_bf16(x: np.ndarray) -> np.ndarray:
     out = np.empty(a.size, dtype=np.uint16)
     _load().orc_f32_to_bf16(_ptr(a), _ptr(out), a.size)
     return out
+
+
+# ---- around the hot path: Mask Tracker (Sec. III-B) and the weight update (Eq. 1) -----------
+
+def mask_from_nonzero(values: np.ndarray, dtype: int = F32):
+    """Mask of the non-zero elements (Eq. 2's Weight != 0).  Returns (mask, prefix, nnz)."""
+    v = np.ascontiguousarray(values, dtype=_elem_dtype(dtype)).reshape(-1)
+    words = mask_words(v.size)
+    mask = np.zeros(max(words, 1), dtype=np.uint64)[:words]
+    prefix = np.zeros(max(words, 1), dtype=np.uint32)[:words]
+    nnz = _load().orc_mask_from_nonzero(_ptr(v), dtype, v.size, _ptr(mask), _ptr(prefix))
+    return mask, prefix, int(nnz)
+
+
+def mask_diff(a: np.ndarray, b: np.ndarray, n: int) -> int:
+    """Number of positions below n at which two bitmasks differ."""
+    a = np.ascontiguousarray(a, dtype=np.uint64)
+    b = np.ascontiguousarray(b, dtype=np.uint64)
+    assert a.size >= mask_words(n) and b.size >= mask_words(n)
+    return int(_load().orc_mask_diff(_ptr(a), _ptr(b), int(n)))
+
+
+class MaskTracker:
+    """The Mask Tracker's bookkeeping (Sec. III-B; Alg. 1 "update sparse mask using Mask Tracker"):
+    keep the previous iteration's mask, compare, and call the pattern stable once it has stayed
+    unchanged for `patience` consecutive comparisons.  The paper says "multiple iterations" without
+    a number: `patience` is the caller's.  The first mask ever seen, and a mask of another length,
+    count as a change."""
+
+    def __init__(self, patience: int):
+        assert patience >= 1
+        self.patience = int(patience)
+        self.prev = None
+        self.prev_n = None
+        self.unchanged = 0
+
+    def update(self, mask: np.ndarray, n: int):
+        """Returns (unchanged_comparisons, stable)."""
+        same = self.prev is not None and self.prev_n == n and mask_diff(self.prev, mask, n) == 0
+        self.unchanged = self.unchanged + 1 if same else 0
+        self.prev = np.array(mask, dtype=np.uint64, copy=True)
+        self.prev_n = n
+        return self.unchanged, self.unchanged >= self.patience
+
+
+def decompress_update(compact: np.ndarray, mask: np.ndarray, weights: np.ndarray, alpha: float,
+                      dtype: int = F32) -> np.ndarray:
+    """x <- x - alpha * g on kept weights (g = next summed compact value), +0 on pruned ones.  Returns the new
+    weights; the input array is left alone."""
+    c = np.ascontiguousarray(compact, dtype=_elem_dtype(dtype)).reshape(-1)
+    w = np.array(weights, dtype=np.float32, copy=True).reshape(-1)
+    used = _load().orc_decompress_update(_ptr(c), dtype, c.size, _ptr(np.ascontiguousarray(mask)),
+                                         ctypes.c_float(alpha), _ptr(w), w.size)
+    if used != c.size:
+        raise ValueError(f"mask holds {used} set bits, compact buffer has {c.size}")
+    return w

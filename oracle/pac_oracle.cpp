@@ -222,4 +222,62 @@ void orc_f32_to_bf16(const float* in, uint16_t* out, uint64_t n) {
     for (uint64_t i = 0; i < n; ++i) out[i] = float_to_bf16_rne(in[i]);
 }
 
+// ---- around the hot path: Mask Tracker and the weight update -------------------------------
+
+// Mask of the non-zero elements of a flat tensor: the (Weight != 0) of Eq. 2, which is also how
+// the Mask Tracker (Sec. III-B, "Mask Tracker mechanism") reads the sparsity pattern off a
+// flattened bucket without names or shapes.  "!= 0" is the IEEE comparison: -0 is zero, NaN
+// and denormals are non-zero.  bf16 values are compared after exact widening.
+// Writes the bitmask (bits >= n zero) and the exclusive prefix; returns the number of set bits.
+uint64_t orc_mask_from_nonzero(const void* values, int dtype, uint64_t n, uint64_t* mask, uint32_t* prefix) {
+    const uint64_t words = (n + 63) / 64;
+    for (uint64_t w = 0; w < words; ++w) mask[w] = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        const float x = dtype == ORC_F32 ? static_cast<const float*>(values)[i]
+                                         : bf16_to_float(static_cast<const uint16_t*>(values)[i]);
+        if (x != 0.0f) mask[i >> 6] |= 1ull << (i & 63);
+    }
+    uint64_t running = 0;
+    for (uint64_t w = 0; w < words; ++w) {
+        prefix[w] = static_cast<uint32_t>(running);
+        running += static_cast<uint64_t>(__builtin_popcountll(mask[w]));
+    }
+    return running;
+}
+
+// Number of positions below n at which two masks differ: the Mask Tracker's comparison of this
+// iteration's mask with the previous one (zero = unchanged).
+uint64_t orc_mask_diff(const uint64_t* a, const uint64_t* b, uint64_t n) {
+    uint64_t diff = 0;
+    for (uint64_t i = 0; i < n; ++i)
+        if (mask_bit(a, i) != mask_bit(b, i)) ++diff;
+    return diff;
+}
+
+// Weight update of Eq. 1 on the sparse model, fused with the decompression of the summed
+// compact buffer: a kept weight becomes x - alpha * g with g the next compact value (widened
+// exactly if bf16) and alpha = eta / n supplied by the caller as one single-precision number;
+// a pruned weight becomes +0 (Prune made it zero and Eq. 2 keeps it there).  Two IEEE single
+// operations per kept element, a multiply and a subtract, each rounded to nearest (no fused
+// multiply-add).  Bits beyond `nnz` compact values take g = +0.
+// Returns the number of set bits met.
+uint64_t orc_decompress_update(const void* compact, int dtype, uint64_t nnz, const uint64_t* mask, float alpha,
+                               float* weights, uint64_t n) {
+    uint64_t next = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        if (!mask_bit(mask, i)) {
+            weights[i] = 0.0f;
+            continue;
+        }
+        float g = 0.0f;
+        if (next < nnz)
+            g = dtype == ORC_F32 ? static_cast<const float*>(compact)[next]
+                                 : bf16_to_float(static_cast<const uint16_t*>(compact)[next]);
+        ++next;
+        const float step = alpha * g;
+        weights[i] = weights[i] - step;
+    }
+    return next;
+}
+
 }  // extern "C"
