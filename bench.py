@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=4, help="workload id 1..5 (4 = the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=1 << 28)
+    ap.add_argument("--no-around", action="store_true",
+                    help="skip the timings of the calls around the hot path (Mask Tracker, fused update)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed loop: a kernel of known traffic "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -191,6 +193,32 @@ def main() -> int:
         "decompress": time_call(lambda: pac.pac_decompress(h, red, mask, prefix, dense_out, nnz0)),
     }
 
+    # Calls around the hot path (Mask Tracker, fused weight update): timed on the same workload,
+    # outside the timed region, reported with their own algorithmic bytes.
+    around = {}
+    if not args.no_around:
+        meta = n // 8 + n // 16
+        nz_out = torch.empty(1, dtype=torch.int64, device=dev)
+        mask2 = torch.empty_like(mask)
+        prefix2 = torch.empty_like(prefix)
+        diff_out = torch.empty(1, dtype=torch.int64, device=dev)
+        state_out = torch.empty(2, dtype=torch.int32, device=dev)
+        pac.pac_decompress(h, red, mask, prefix, dense_out, nnz0)
+        tracker = pac.MaskTracker(ctx, max_elems=n, patience=2)
+        w_copy = wl.weights.clone()
+        calls = {
+            "mask_from_nonzero": (lambda: pac.pac_mask_from_nonzero(h, dense_out, mask2, prefix2, nz_out), e * n + meta),
+            "mask_equal": (lambda: pac.pac_mask_equal(h, mask, mask2, n, diff_out), 2 * (n // 8)),
+            "tracker_update": (lambda: tracker.update(mask, n, state_out), 3 * (n // 8)),
+            "decompress_update": (lambda: pac.pac_decompress_update(h, red, mask, prefix, 1e-3, w_copy, nnz0),
+                                  e * nnz0 + meta + 8 * n),
+        }
+        for name, (fn, nbytes) in calls.items():
+            ms = time_call(fn)
+            around[name] = {"ms": round(ms, 4), "algorithmic_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+        tracker.close()
+        del w_copy, mask2, prefix2
+
     k_avg = sum(k_by_phase[(args.warmup + t) % len(schedule)] for t in range(args.steps)) / args.steps
     alg = algorithmic_bytes(n, int(k_avg), W, e)
     step_alg = alg["build_mask"] + W * alg["compress"] + alg["reduce_local"] + alg["decompress"]
@@ -230,6 +258,8 @@ def main() -> int:
             "avg_launch_ms": round(compress_ms, 5),
         },
     }
+    if around:
+        result["around_the_path"] = around
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_elems)
     ctx.close()

@@ -117,6 +117,53 @@ pac_status pac_decompress(pac_ctx* ctx, const void* d_compact, pac_dtype dtype, 
                           const uint64_t* d_mask, const uint32_t* d_prefix,
                           void* d_dense_out, uint64_t n, void* hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Around the hot path: Mask Tracker and weight update.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Mask of the non-zero elements of a flat tensor: the (Weight != 0) of paper Eq. 2, which is how the
+ * Mask Tracker (Sec. III-B "Mask Tracker mechanism") reads the sparsity pattern off a flattened
+ * bucket.  Bit i is set iff d_values[i] != 0 as an IEEE comparison (both zeros are zero; NaN and
+ * denormals are not).  Writes d_mask[ceil(n/64)] (bits >= n zero), d_prefix[ceil(n/64)] and, if
+ * d_nnz_out is not NULL, the number of set bits to that DEVICE location (the count depends on the
+ * data, so the host learns it only by copying it back).  n must not exceed the context's max_elems.
+ * Uses the context's scratch, like pac_build_mask. */
+pac_status pac_mask_from_nonzero(pac_ctx* ctx, const void* d_values, pac_dtype dtype, uint64_t n,
+                                 uint64_t* d_mask, uint32_t* d_prefix, uint64_t* d_nnz_out,
+                                 void* hip_stream);
+
+/* Mask Tracker comparison (Sec. III-B: the mask of this iteration against the previous one):
+ * *d_diff_bits_out (DEVICE) = number of positions below n at which the two bitmasks differ;
+ * 0 means the sparsity pattern is unchanged.  Bits at and beyond n are ignored. */
+pac_status pac_mask_equal(pac_ctx* ctx, const uint64_t* d_mask_a, const uint64_t* d_mask_b, uint64_t n,
+                          uint64_t* d_diff_bits_out, void* hip_stream);
+
+/* Mask Tracker bookkeeping (Sec. III-B; Alg. 1 "Update sparse mask using Mask Tracker" / "if mask is
+ * stable"): keeps the previous iteration's mask on the device and counts consecutive comparisons
+ * that found no difference.  The pattern is "stable" once that count reaches `patience` (the paper
+ * says "multiple iterations" and gives no number: the caller chooses, >= 1).  The first mask a
+ * tracker sees, and a mask of another length n, count as a change.
+ * pac_tracker_update enqueues compare + copy on the stream and writes {unchanged, stable} to
+ * d_state_out (DEVICE uint32[2], may be NULL).  The caller decides between the compressed and the
+ * dense synchronisation from that state (for the dense one, pac_reduce_local sums W dense buffers
+ * of n elements just as it sums compact ones).  Calls on one tracker must be issued in stream order.
+ * The tracker belongs to the context and must be destroyed before it. */
+typedef struct pac_tracker pac_tracker;
+pac_status pac_tracker_create(pac_ctx* ctx, uint64_t max_elems, uint32_t patience, pac_tracker** out);
+pac_status pac_tracker_update(pac_tracker* tracker, const uint64_t* d_mask, uint64_t n,
+                              uint32_t* d_state_out, void* hip_stream);
+pac_status pac_tracker_destroy(pac_tracker* tracker);
+
+/* Weight update of paper Eq. 1 on the sparse model, fused with pac_decompress: for every set bit i,
+ * d_weights[i] <- d_weights[i] - alpha * d_reduced[slot(i)] (alpha = eta / n of Eq. 1, computed by
+ * the caller; one IEEE single multiply, then one subtract, each rounded to nearest; bf16 sums are
+ * widened exactly; a NaN result is some NaN, its sign and payload are the hardware's); for every
+ * clear bit, d_weights[i] <- +0 (the pruned weights stay zero, Eq. 2).
+ * The dense gradient is never materialised.  No read at or beyond d_reduced[nnz]. */
+pac_status pac_decompress_update(pac_ctx* ctx, const void* d_reduced, pac_dtype dtype, uint64_t nnz,
+                                 const uint64_t* d_mask, const uint32_t* d_prefix, float alpha,
+                                 float* d_weights, uint64_t n, void* hip_stream);
+
 /* Test hook: lower the capacity of the candidate list pac_build_mask uses between its selection
  * passes (elements; clamped to what pac_create allocated).  Scopes whose candidates do not fit take
  * the slower in-place selection; results are identical.  Exists so that tests can reach that branch

@@ -8,4 +8,6 @@ from .binding import (  # noqa: F401
     PAC_BF16, PAC_F32, PacError, PacContext, library_path, load_library,
     pac_build_mask, pac_compress, pac_create, pac_debug_set_candidate_capacity, pac_decompress,
     pac_destroy, pac_keep_count, pac_last_error, pac_mask_words, pac_reduce_local,
+    MaskTracker, pac_decompress_update, pac_mask_equal, pac_mask_from_nonzero, pac_tracker_create,
+    pac_tracker_destroy, pac_tracker_update,
 )

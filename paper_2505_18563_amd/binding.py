@@ -62,6 +62,18 @@ def load_library() -> ctypes.CDLL:
     lib.pac_decompress.argtypes = [vp, vp, i32, u64, vp, vp, vp, u64, vp]
     lib.pac_debug_set_candidate_capacity.restype = i32
     lib.pac_debug_set_candidate_capacity.argtypes = [vp, u64]
+    lib.pac_mask_from_nonzero.restype = i32
+    lib.pac_mask_from_nonzero.argtypes = [vp, vp, i32, u64, vp, vp, vp, vp]
+    lib.pac_mask_equal.restype = i32
+    lib.pac_mask_equal.argtypes = [vp, vp, vp, u64, vp, vp]
+    lib.pac_tracker_create.restype = i32
+    lib.pac_tracker_create.argtypes = [vp, u64, u32, ctypes.POINTER(vp)]
+    lib.pac_tracker_update.restype = i32
+    lib.pac_tracker_update.argtypes = [vp, vp, u64, vp, vp]
+    lib.pac_tracker_destroy.restype = i32
+    lib.pac_tracker_destroy.argtypes = [vp]
+    lib.pac_decompress_update.restype = i32
+    lib.pac_decompress_update.argtypes = [vp, vp, i32, u64, vp, vp, ctypes.c_float, vp, u64, vp]
     _lib = lib
     return lib
 
@@ -186,6 +198,74 @@ def pac_decompress(ctx, compact: torch.Tensor, mask: torch.Tensor, prefix: torch
     _check(ctx, st)
 
 
+def pac_mask_from_nonzero(ctx, values: torch.Tensor, mask: torch.Tensor, prefix: torch.Tensor,
+                          nnz_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    """values fp32 or bf16 [n]; nnz_out: device int64 [1] (the count stays on the device)."""
+    dt = _dtype_code(values)
+    n = values.numel()
+    words = (n + 63) // 64
+    if mask.dtype != torch.int64 or prefix.dtype != torch.int32:
+        raise TypeError("mask must be int64 and prefix int32")
+    if mask.numel() < words or prefix.numel() < words:
+        raise ValueError("mask/prefix too short")
+    if nnz_out is not None and (nnz_out.dtype != torch.int64 or nnz_out.numel() < 1):
+        raise TypeError("nnz_out must be an int64 tensor")
+    st = load_library().pac_mask_from_nonzero(ctx, _dev_ptr(values) if n else 0, dt, n, _dev_ptr(mask) if n else 0,
+                                              _dev_ptr(prefix) if n else 0, _dev_ptr(nnz_out), _stream_ptr(stream))
+    _check(ctx, st)
+
+
+def pac_mask_equal(ctx, mask_a: torch.Tensor, mask_b: torch.Tensor, n: int, diff_out: torch.Tensor,
+                   stream=None) -> None:
+    """diff_out: device int64 [1], receives the number of differing positions below n."""
+    words = (int(n) + 63) // 64
+    if mask_a.dtype != torch.int64 or mask_b.dtype != torch.int64 or diff_out.dtype != torch.int64:
+        raise TypeError("masks and diff_out must be int64")
+    if mask_a.numel() < words or mask_b.numel() < words or diff_out.numel() < 1:
+        raise ValueError("tensor too short")
+    st = load_library().pac_mask_equal(ctx, _dev_ptr(mask_a) if n else 0, _dev_ptr(mask_b) if n else 0, int(n),
+                                       _dev_ptr(diff_out), _stream_ptr(stream))
+    _check(ctx, st)
+
+
+def pac_tracker_create(ctx, max_elems: int, patience: int):
+    out = ctypes.c_void_p()
+    _check(ctx, load_library().pac_tracker_create(ctx, int(max_elems), int(patience), ctypes.byref(out)))
+    return out
+
+
+def pac_tracker_update(ctx, tracker, mask: torch.Tensor, n: int, state_out: Optional[torch.Tensor] = None,
+                       stream=None) -> None:
+    """state_out: device int32 [2], receives {unchanged comparisons, stable}."""
+    if mask.dtype != torch.int64:
+        raise TypeError("mask must be int64")
+    if mask.numel() < (int(n) + 63) // 64:
+        raise ValueError("mask too short")
+    if state_out is not None and (state_out.dtype != torch.int32 or state_out.numel() < 2):
+        raise TypeError("state_out must be an int32 tensor of 2 elements")
+    st = load_library().pac_tracker_update(tracker, _dev_ptr(mask) if n else 0, int(n), _dev_ptr(state_out),
+                                           _stream_ptr(stream))
+    _check(ctx, st)
+
+
+def pac_tracker_destroy(tracker) -> None:
+    load_library().pac_tracker_destroy(tracker)
+
+
+def pac_decompress_update(ctx, reduced: torch.Tensor, mask: torch.Tensor, prefix: torch.Tensor, alpha: float,
+                          weights: torch.Tensor, nnz: int, stream=None) -> None:
+    """weights fp32 [n], updated in place."""
+    dt = _dtype_code(reduced)
+    if weights.dtype != torch.float32:
+        raise TypeError("weights must be float32")
+    if reduced.numel() < nnz:
+        raise ValueError("reduced buffer too short")
+    st = load_library().pac_decompress_update(ctx, _dev_ptr(reduced), dt, int(nnz), _dev_ptr(mask), _dev_ptr(prefix),
+                                              ctypes.c_float(alpha), _dev_ptr(weights), weights.numel(),
+                                              _stream_ptr(stream))
+    _check(ctx, st)
+
+
 # ------------------------------------------------------------------------------ convenience
 class PacContext:
     """Owns one pac_ctx and allocates outputs with torch; the arithmetic stays in the library."""
@@ -252,3 +332,52 @@ class PacContext:
             out = torch.empty(n, dtype=compact.dtype, device=self._dev())
         pac_decompress(self.handle, compact, mask, prefix, out, nnz, stream)
         return out
+
+    def mask_from_nonzero(self, values, mask=None, prefix=None, nnz_out=None, stream=None):
+        """Returns (mask, prefix, nnz_out); nnz_out is a device int64 tensor of one element."""
+        words = (values.numel() + 63) // 64
+        if mask is None:
+            mask = torch.empty(words, dtype=torch.int64, device=self._dev())
+        if prefix is None:
+            prefix = torch.empty(words, dtype=torch.int32, device=self._dev())
+        if nnz_out is None:
+            nnz_out = torch.empty(1, dtype=torch.int64, device=self._dev())
+        pac_mask_from_nonzero(self.handle, values, mask, prefix, nnz_out, stream)
+        return mask, prefix, nnz_out
+
+    def mask_equal(self, mask_a, mask_b, n, diff_out=None, stream=None) -> torch.Tensor:
+        if diff_out is None:
+            diff_out = torch.empty(1, dtype=torch.int64, device=self._dev())
+        pac_mask_equal(self.handle, mask_a, mask_b, n, diff_out, stream)
+        return diff_out
+
+    def decompress_update(self, reduced, mask, prefix, alpha, weights, nnz: Optional[int] = None, stream=None):
+        if nnz is None:
+            nnz = reduced.numel()
+        pac_decompress_update(self.handle, reduced, mask, prefix, alpha, weights, nnz, stream)
+        return weights
+
+
+class MaskTracker:
+    """Owns one pac_tracker of a context."""
+
+    def __init__(self, ctx: PacContext, max_elems: int, patience: int):
+        self.ctx = ctx
+        self.handle = pac_tracker_create(ctx.handle, max_elems, patience)
+
+    def update(self, mask, n, state_out=None, stream=None) -> torch.Tensor:
+        if state_out is None:
+            state_out = torch.empty(2, dtype=torch.int32, device=self.ctx._dev())
+        pac_tracker_update(self.ctx.handle, self.handle, mask, n, state_out, stream)
+        return state_out
+
+    def close(self) -> None:
+        if self.handle is not None:
+            pac_tracker_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -37,6 +37,16 @@ struct pac_ctx {
     char err[256] = "";
 };
 
+struct pac_tracker {
+    pac_ctx* ctx = nullptr;
+    unsigned long long* prev = nullptr;      // the previous iteration's mask (device)
+    pac::TrackerState* state = nullptr;      // counters (device)
+    uint64_t max_elems = 0;
+    uint32_t patience = 1;
+    bool has_prev = false;
+    uint64_t prev_n = 0;
+};
+
 namespace {
 
 pac_status fail(pac_ctx* ctx, pac_status code, const char* fmt, ...) {
@@ -358,6 +368,142 @@ pac_status pac_reduce_local(pac_ctx* ctx, const void* const* h_d_compact, uint32
     if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_reduce_local: hipSetDevice: %s", hipGetErrorString(guard.status));
     hipError_t r = pac::launch_reduce(bufs, W, (int)dtype, (uint32_t)nnz, d_out, static_cast<hipStream_t>(hip_stream));
     if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_reduce_local: launch: %s", hipGetErrorString(r));
+    return PAC_OK;
+}
+
+// ---- Mask Tracker and weight update ----------------------------------------------------------
+
+pac_status pac_mask_from_nonzero(pac_ctx* ctx, const void* d_values, pac_dtype dtype, uint64_t n, uint64_t* d_mask,
+                                 uint32_t* d_prefix, uint64_t* d_nnz_out, void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    const char* who = "pac_mask_from_nonzero";
+    if (dtype != PAC_F32 && dtype != PAC_BF16) return fail(ctx, PAC_ERR_ARG, "%s: unknown dtype %d", who, (int)dtype);
+    if (n > ctx->max_elems) return fail(ctx, PAC_ERR_RANGE, "%s: n=%llu exceeds the context's max_elems=%llu", who,
+                                        (unsigned long long)n, (unsigned long long)ctx->max_elems);
+    if (n > 0 && (!d_values || !d_mask || !d_prefix)) return fail(ctx, PAC_ERR_ARG, "%s: NULL device pointer", who);
+    if (!is_aligned(d_values, elem_size(dtype)) || !is_aligned(d_mask, 8) || !is_aligned(d_prefix, 4) ||
+        !is_aligned(d_nnz_out, 8))
+        return fail(ctx, PAC_ERR_ALIGN, "%s: pointer not aligned to its element size", who);
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: hipSetDevice: %s", who, hipGetErrorString(guard.status));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned long long* total = reinterpret_cast<unsigned long long*>(d_nnz_out);
+    hipError_t r = hipSuccess;
+    if (n == 0) {
+        // an empty mask has no words; the count is still defined
+        if (total) r = pac::launch_mask_diff(nullptr, nullptr, 0, total, nullptr, stream);   // writes 0
+    } else {
+        r = pac::launch_nonzero_mask(d_values, (int)dtype, (uint32_t)n, reinterpret_cast<unsigned long long*>(d_mask), stream);
+        if (r == hipSuccess)
+            r = pac::launch_prefix_scan(ctx->scratch, reinterpret_cast<const unsigned long long*>(d_mask),
+                                        (uint32_t)pac_mask_words(n), d_prefix, total, stream);
+    }
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: launch: %s", who, hipGetErrorString(r));
+    return PAC_OK;
+}
+
+pac_status pac_mask_equal(pac_ctx* ctx, const uint64_t* d_mask_a, const uint64_t* d_mask_b, uint64_t n,
+                          uint64_t* d_diff_bits_out, void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    const char* who = "pac_mask_equal";
+    if (n >= (1ull << 32)) return fail(ctx, PAC_ERR_RANGE, "%s: n=%llu must be below 2^32", who, (unsigned long long)n);
+    if (!d_diff_bits_out || (n > 0 && (!d_mask_a || !d_mask_b))) return fail(ctx, PAC_ERR_ARG, "%s: NULL device pointer", who);
+    if (!is_aligned(d_mask_a, 8) || !is_aligned(d_mask_b, 8) || !is_aligned(d_diff_bits_out, 8))
+        return fail(ctx, PAC_ERR_ALIGN, "%s: pointer not aligned to 8 bytes", who);
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: hipSetDevice: %s", who, hipGetErrorString(guard.status));
+    hipError_t r = pac::launch_mask_diff(reinterpret_cast<const unsigned long long*>(d_mask_a),
+                                         reinterpret_cast<const unsigned long long*>(d_mask_b), (uint32_t)n,
+                                         reinterpret_cast<unsigned long long*>(d_diff_bits_out), nullptr,
+                                         static_cast<hipStream_t>(hip_stream));
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: launch: %s", who, hipGetErrorString(r));
+    return PAC_OK;
+}
+
+pac_status pac_tracker_create(pac_ctx* ctx, uint64_t max_elems, uint32_t patience, pac_tracker** out) {
+    if (!ctx) return PAC_ERR_ARG;
+    if (!out) return fail(ctx, PAC_ERR_ARG, "pac_tracker_create: out is NULL");
+    *out = nullptr;
+    if (max_elems == 0 || max_elems >= (1ull << 32))
+        return fail(ctx, PAC_ERR_RANGE, "pac_tracker_create: max_elems must be in [1, 2^32)");
+    if (patience == 0) return fail(ctx, PAC_ERR_RANGE, "pac_tracker_create: patience must be at least 1");
+    pac_tracker* t = new (std::nothrow) pac_tracker();
+    if (!t) return fail(ctx, PAC_ERR_NOMEM, "pac_tracker_create: host allocation failed");
+    t->ctx = ctx;
+    t->max_elems = max_elems;
+    t->patience = patience;
+    DeviceGuard guard(ctx->device);
+    hipError_t r = guard.status;
+    if (r == hipSuccess) r = hipMalloc((void**)&t->prev, (size_t)pac_mask_words(max_elems) * 8);
+    if (r == hipSuccess) r = hipMalloc((void**)&t->state, sizeof(pac::TrackerState));
+    if (r == hipSuccess) r = hipMemset(t->state, 0, sizeof(pac::TrackerState));
+    if (r == hipSuccess) r = hipDeviceSynchronize();
+    if (r != hipSuccess) {
+        (void)hipFree(t->prev);
+        (void)hipFree(t->state);
+        delete t;
+        return fail(ctx, PAC_ERR_NOMEM, "pac_tracker_create: device allocation: %s", hipGetErrorString(r));
+    }
+    *out = t;
+    return PAC_OK;
+}
+
+pac_status pac_tracker_update(pac_tracker* t, const uint64_t* d_mask, uint64_t n, uint32_t* d_state_out,
+                              void* hip_stream) {
+    if (!t) return PAC_ERR_ARG;
+    pac_ctx* ctx = t->ctx;
+    const char* who = "pac_tracker_update";
+    if (n > t->max_elems) return fail(ctx, PAC_ERR_RANGE, "%s: n=%llu exceeds the tracker's max_elems=%llu", who,
+                                      (unsigned long long)n, (unsigned long long)t->max_elems);
+    if (n > 0 && !d_mask) return fail(ctx, PAC_ERR_ARG, "%s: d_mask is NULL", who);
+    if (!is_aligned(d_mask, 8) || !is_aligned(d_state_out, 4)) return fail(ctx, PAC_ERR_ALIGN, "%s: misaligned pointer", who);
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: hipSetDevice: %s", who, hipGetErrorString(guard.status));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const unsigned long long* m = reinterpret_cast<const unsigned long long*>(d_mask);
+    const bool fresh = !t->has_prev || t->prev_n != n;
+    hipError_t r;
+    if (fresh) {
+        r = pac::launch_mask_copy(m, t->prev, (uint32_t)pac_mask_words(n), stream);
+    } else {
+        // compare with the previous mask and replace it in one pass
+        r = pac::launch_mask_diff(t->prev, m, (uint32_t)n, &t->state->diff, t->prev, stream);
+    }
+    if (r == hipSuccess) r = pac::launch_tracker_finalize(t->state, t->patience, fresh ? 1u : 0u, d_state_out, stream);
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: launch: %s", who, hipGetErrorString(r));
+    t->has_prev = true;
+    t->prev_n = n;
+    return PAC_OK;
+}
+
+pac_status pac_tracker_destroy(pac_tracker* t) {
+    if (!t) return PAC_OK;
+    DeviceGuard guard(t->ctx->device);
+    (void)hipDeviceSynchronize();
+    (void)hipFree(t->prev);
+    (void)hipFree(t->state);
+    delete t;
+    return PAC_OK;
+}
+
+pac_status pac_decompress_update(pac_ctx* ctx, const void* d_reduced, pac_dtype dtype, uint64_t nnz,
+                                 const uint64_t* d_mask, const uint32_t* d_prefix, float alpha, float* d_weights,
+                                 uint64_t n, void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    const char* who = "pac_decompress_update";
+    if (dtype != PAC_F32 && dtype != PAC_BF16) return fail(ctx, PAC_ERR_ARG, "%s: unknown dtype %d", who, (int)dtype);
+    if (n >= (1ull << 32)) return fail(ctx, PAC_ERR_RANGE, "%s: n=%llu must be below 2^32", who, (unsigned long long)n);
+    if (nnz > n) return fail(ctx, PAC_ERR_COUNT, "%s: nnz=%llu exceeds n=%llu", who, (unsigned long long)nnz, (unsigned long long)n);
+    if (n == 0) return PAC_OK;
+    if (!d_weights || !d_mask || !d_prefix || (nnz > 0 && !d_reduced)) return fail(ctx, PAC_ERR_ARG, "%s: NULL device pointer", who);
+    if (!is_aligned(d_weights, 4) || !is_aligned(d_reduced, elem_size(dtype)) || !is_aligned(d_mask, 8) || !is_aligned(d_prefix, 4))
+        return fail(ctx, PAC_ERR_ALIGN, "%s: pointer not aligned to its element size", who);
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: hipSetDevice: %s", who, hipGetErrorString(guard.status));
+    hipError_t r = pac::launch_decompress_update(d_reduced, (int)dtype, (uint32_t)nnz,
+                                                 reinterpret_cast<const unsigned long long*>(d_mask), d_prefix, alpha,
+                                                 d_weights, (uint32_t)n, static_cast<hipStream_t>(hip_stream));
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: launch: %s", who, hipGetErrorString(r));
     return PAC_OK;
 }
 

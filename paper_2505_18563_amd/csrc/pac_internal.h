@@ -101,11 +101,40 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
                              uint64_t sampled_elems, unsigned long long* d_mask, uint32_t* d_prefix, int num_cu,
                              hipStream_t stream);
 
+// prefix[j] = set bits in words < j of any mask of at most the context's max_elems bits;
+// *d_total_out (device, may be null) receives the number of set bits.  Uses the context's scan scratch.
+hipError_t launch_prefix_scan(const MaskScratch& s, const unsigned long long* d_mask, uint32_t words,
+                              uint32_t* d_prefix, unsigned long long* d_total_out, hipStream_t stream);
+
 hipError_t launch_compress(const void* d_grad, int dtype, uint32_t n, const unsigned long long* d_mask,
                            const uint32_t* d_prefix, void* d_compact, uint32_t nnz, hipStream_t stream);
 
 hipError_t launch_decompress(const void* d_compact, int dtype, uint32_t nnz, const unsigned long long* d_mask,
                              const uint32_t* d_prefix, void* d_dense, uint32_t n, hipStream_t stream);
+
+// x <- x - alpha * g on kept weights (g = the next value of the summed compact buffer), +0 on pruned ones.
+hipError_t launch_decompress_update(const void* d_compact, int dtype, uint32_t nnz, const unsigned long long* d_mask,
+                                    const uint32_t* d_prefix, float alpha, float* d_weights, uint32_t n,
+                                    hipStream_t stream);
+
+// Mask Tracker kernels (pac_track.hip).
+hipError_t launch_nonzero_mask(const void* d_values, int dtype, uint32_t n, unsigned long long* d_mask,
+                               hipStream_t stream);
+// *d_diff_out = number of positions below n where the masks differ; if d_copy_to is not null, mask b is
+// copied there in the same pass (d_copy_to may be mask a).
+hipError_t launch_mask_diff(const unsigned long long* d_a, const unsigned long long* d_b, uint32_t n,
+                            unsigned long long* d_diff_out, unsigned long long* d_copy_to, hipStream_t stream);
+hipError_t launch_mask_copy(const unsigned long long* d_src, unsigned long long* d_dst, uint32_t words,
+                            hipStream_t stream);
+struct TrackerState {
+    unsigned long long diff;   // scratch of the comparison
+    uint32_t unchanged;        // consecutive comparisons that found no difference
+    uint32_t stable;           // unchanged >= patience
+};
+// After a comparison (fresh = 0) or a first / resized observation (fresh = 1): updates the counters and
+// writes {unchanged, stable} to d_state_out (device uint32[2], may be null).
+hipError_t launch_tracker_finalize(TrackerState* d_state, uint32_t patience, uint32_t fresh, uint32_t* d_state_out,
+                                   hipStream_t stream);
 
 struct WorkerPtrs {
     const void* p[64];

@@ -799,7 +799,6 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
     u64 prefix = (u64)(st->lo + (st->bin1 << st->sh1)) << 32;
     uint32_t krem = st->krem1;
     const uint32_t begin = seg[s].begin, end = seg[s].end;
-    const uint32_t cnt1 = st->cnt1;
     if (threadIdx.x == 0) { found[0] = 0; found[1] = 0; gathered = 0; }
     __syncthreads();
     const bool from_list = !glob->overflow && !glob->match_overflow && !st->in_place && !st->heavy;
@@ -919,7 +918,8 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
 
 __global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __restrict__ mask, uint32_t words,
                                                                    u64* __restrict__ tile_state, Globals* glob,
-                                                                   uint32_t* __restrict__ prefix) {
+                                                                   uint32_t* __restrict__ prefix,
+                                                                   u64* __restrict__ total_out) {
     __shared__ uint32_t ex_lds[kScanIters][kScanBlock];
     __shared__ uint32_t wave_totals[kScanWaves];
     __shared__ uint32_t sh_tile, sh_base;
@@ -1001,6 +1001,8 @@ __global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __
     }
     __syncthreads();
     const uint32_t base = sh_base + wave_off;
+    // the last tile knows the number of set bits of the whole mask
+    if (total_out != nullptr && tile == gridDim.x - 1 && threadIdx.x == 0) *total_out = (u64)sh_base + tile_total;
 #pragma unroll
     for (uint32_t it = 0; it < kScanIters; ++it) {
         const u64 w0 = wave_first + it * 128u + lane * 2u;
@@ -1011,6 +1013,13 @@ __global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __
             prefix[w0] = a;
         }
     }
+}
+
+// Clears the scan's tile states and ticket for a scan that does not follow a mask build.
+__global__ void scan_reset_kernel(u64* __restrict__ tile_state, uint32_t tiles, Globals* glob) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i <= tiles) tile_state[i] = 0;
+    if (i == 0) { glob->scan_ticket = 0; glob->scan_stalled = 0; }
 }
 
 inline uint32_t div_up_u64(u64 a, u64 b) { return (uint32_t)((a + b - 1) / b); }
@@ -1079,7 +1088,18 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
 
     const uint32_t scan_tiles = div_up_u64(words, kScanTile);
     hipLaunchKernelGGL(scan_lookback_kernel, dim3(scan_tiles), dim3(kScanBlock), 0, stream, d_mask, words,
-                       s.tile_state, s.glob, d_prefix);
+                       s.tile_state, s.glob, d_prefix, static_cast<u64*>(nullptr));
+    return hipGetLastError();
+}
+
+hipError_t launch_prefix_scan(const MaskScratch& s, const unsigned long long* d_mask, uint32_t words,
+                              uint32_t* d_prefix, unsigned long long* d_total_out, hipStream_t stream) {
+    if (words == 0) return hipSuccess;
+    const uint32_t scan_tiles = div_up_u64(words, kScanTile);
+    hipLaunchKernelGGL(scan_reset_kernel, dim3(div_up_u64(scan_tiles + 1, 256)), dim3(256), 0, stream, s.tile_state,
+                       scan_tiles, s.glob);
+    hipLaunchKernelGGL(scan_lookback_kernel, dim3(scan_tiles), dim3(kScanBlock), 0, stream, d_mask, words,
+                       s.tile_state, s.glob, d_prefix, d_total_out);
     return hipGetLastError();
 }
 

@@ -322,6 +322,144 @@ __global__ __launch_bounds__(kBlock) void decompress_scalar_kernel(const T* __re
     dense[i] = val;
 }
 
+// --------------------------------------------------------------- decompress + weight update
+// Eq. 1 on the sparse model, fused into the scatter: the dense gradient is never written.  Same
+// tile scheme as decompress with fp32 weight chunks (4 weights per lane and step): the tile's
+// compact range goes through the wave's LDS staging area, every lane reads its chunk of weights,
+// subtracts alpha * g where the mask bit is set (a multiply and a subtract, each rounded on its own)
+// and stores +0 where it is not.
+template <typename T>
+__device__ __forceinline__ float widen(T v);
+template <>
+__device__ __forceinline__ float widen<uint32_t>(uint32_t v) { return __uint_as_float(v); }
+template <>
+__device__ __forceinline__ float widen<uint16_t>(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+
+template <typename T, int U>
+struct UpdateTile {
+    static constexpr uint32_t E = 4;                      // weights per 16-byte chunk
+    static constexpr uint32_t EC = 16 / sizeof(T);        // compact elements per 16 bytes
+    static constexpr uint32_t kChunks = 64 * U;
+    static constexpr uint32_t kElems = kChunks * E;
+    static constexpr uint32_t kWords = kElems / 64;
+    static constexpr uint32_t kStage = kElems + 2 * EC;
+};
+
+template <typename T, int U>
+__global__ __launch_bounds__(kPackBlock) void update_tile_kernel(const T* __restrict__ compact, uint32_t nnz,
+                                                                 const unsigned long long* __restrict__ mask,
+                                                                 const uint32_t* __restrict__ prefix, float alpha,
+                                                                 u32x4* __restrict__ weights, uint32_t n) {
+    typedef UpdateTile<T, U> G;
+    constexpr uint32_t E = G::E, EC = G::EC;
+    __shared__ __attribute__((aligned(16))) T stage[kPackWaves][G::kStage];
+
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t tile = blockIdx.x * kPackWaves + wave;
+    if ((unsigned long long)tile * G::kElems >= n) return;
+    const uint32_t n_chunks = n / E;
+    const uint32_t words = (uint32_t)(((unsigned long long)n + 63) >> 6);
+    const uint32_t chunk0 = tile * G::kChunks;
+
+    u32x4 x[U];
+    unsigned long long word[U];
+    uint32_t pre[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t q = chunk0 + (uint32_t)u * 64 + lane;
+        word[u] = 0;
+        pre[u] = 0;
+        x[u] = (u32x4){0, 0, 0, 0};
+        if (q < n_chunks) {
+            x[u] = __builtin_nontemporal_load(weights + q);
+            const uint32_t w = (q * E) >> 6;
+            word[u] = mask[w];
+            pre[u] = prefix[w];
+        }
+    }
+
+    const uint32_t w0 = tile * G::kWords;
+    const uint32_t w1 = w0 + G::kWords;
+    const uint32_t s0 = prefix[w0];
+    const uint32_t s1 = w1 < words ? prefix[w1] : nnz;
+    // Inconsistent metadata: read no compact value, kept weights of the tile stay as they are.
+    const bool sane = s0 <= s1 && s1 <= nnz && s1 - s0 <= G::kElems;
+    const uint32_t count = sane ? s1 - s0 : 0u;
+    const uint32_t ph = phase_of(compact + s0);
+    T* my = stage[wave];
+
+    if (count != 0) {
+        const T* gbase = compact + s0 - ph;
+        const uint32_t a = ph, b = ph + count;
+        uint32_t h_end = (a + EC - 1u) & ~(EC - 1u);
+        if (h_end > b) h_end = b;
+        if (lane < h_end - a) my[a + lane] = gbase[a + lane];
+        for (uint32_t c = h_end / EC + lane; c < b / EC; c += 64)
+            *reinterpret_cast<u32x4*>(my + c * EC) = *reinterpret_cast<const u32x4*>(gbase + c * EC);
+        uint32_t t0 = b & ~(EC - 1u);
+        if (t0 < h_end) t0 = h_end;
+        if (lane < b - t0) my[t0 + lane] = gbase[t0 + lane];
+    }
+    wave_lds_sync();
+
+    auto updated = [&](uint32_t xbits, bool kept, const T* p) -> uint32_t {
+        if (!kept) return 0u;
+        const float g = p ? widen<T>(*p) : 0.0f;
+        return __float_as_uint(__fsub_rn(__uint_as_float(xbits), __fmul_rn(alpha, g)));
+    };
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t q = chunk0 + (uint32_t)u * 64 + lane;
+        if (q < n_chunks) {
+            const uint32_t bitoff = (q * E) & 63u;
+            const uint32_t sub = (uint32_t)(word[u] >> bitoff) & 0xFu;
+            const uint32_t pos = pre[u] + popc64(word[u] & ((1ull << bitoff) - 1ull)) - s0 + ph;
+            // compact values this chunk may read: LDS [pos, pos + popc(sub)) inside [ph, ph + count)
+            const bool readable = sane && pos <= ph + count && (uint32_t)__popc(sub) <= ph + count - pos;
+            const T* p = my + pos;
+            u32x4 o;
+            o.x = updated(x[u].x, sub & 1u, readable ? p : nullptr); p += (sub & 1u);
+            o.y = updated(x[u].y, sub & 2u, readable ? p : nullptr); p += (sub >> 1) & 1u;
+            o.z = updated(x[u].z, sub & 4u, readable ? p : nullptr); p += (sub >> 2) & 1u;
+            o.w = updated(x[u].w, sub & 8u, readable ? p : nullptr);
+            __builtin_nontemporal_store(o, weights + q);
+        }
+    }
+    if (tile == n_chunks / G::kChunks) {   // the elements after the last whole chunk
+        const uint32_t i = n_chunks * E + lane;
+        if (lane < E && i < n) {
+            float* wts = reinterpret_cast<float*>(weights);
+            const unsigned long long wd = mask[i >> 6];
+            float val = 0.0f;
+            if ((wd >> (i & 63u)) & 1ull) {
+                const uint32_t pos = prefix[i >> 6] + popc64(wd & ((1ull << (i & 63u)) - 1ull)) - s0 + ph;
+                const float g = (sane && pos < ph + count) ? widen<T>(my[pos]) : 0.0f;
+                val = __fsub_rn(wts[i], __fmul_rn(alpha, g));
+            }
+            wts[i] = val;
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void update_scalar_kernel(const T* __restrict__ compact, uint32_t nnz,
+                                                               const unsigned long long* __restrict__ mask,
+                                                               const uint32_t* __restrict__ prefix, float alpha,
+                                                               float* __restrict__ weights, uint32_t n) {
+    const unsigned long long i = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const unsigned long long wd = mask[i >> 6];
+    const uint32_t b = (uint32_t)i & 63u;
+    float val = 0.0f;
+    if ((wd >> b) & 1ull) {
+        const uint32_t slot = prefix[i >> 6] + popc64(wd & ((1ull << b) - 1ull));
+        const float g = slot < nnz ? widen<T>(compact[slot]) : 0.0f;
+        val = __fsub_rn(weights[i], __fmul_rn(alpha, g));
+    }
+    weights[i] = val;
+}
+
 // ---------------------------------------------------------------------------------------- sum
 // bf16 <-> fp32 on bit patterns.  Narrowing is round-to-nearest-even; a NaN keeps its sign and
 // top payload bits and gets the quiet bit, so it cannot round into infinity.
@@ -491,6 +629,32 @@ hipError_t launch_decompress(const void* d_compact, int dtype, uint32_t nnz, con
             hipLaunchKernelGGL((decompress_scalar_kernel<uint16_t>), dim3(blocks), dim3(kBlock), 0, stream,
                                static_cast<const uint16_t*>(d_compact), nnz, d_mask, d_prefix,
                                static_cast<uint16_t*>(d_dense), n);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_decompress_update(const void* d_compact, int dtype, uint32_t nnz, const unsigned long long* d_mask,
+                                    const uint32_t* d_prefix, float alpha, float* d_weights, uint32_t n,
+                                    hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    if (aligned16(d_weights)) {
+        const uint32_t tiles = div_up(n, UpdateTile<uint32_t, kPackU>::kElems);   // same for both payload types
+        if (dtype == 0)
+            hipLaunchKernelGGL((update_tile_kernel<uint32_t, kPackU>), dim3(div_up(tiles, kPackWaves)), dim3(kPackBlock),
+                               0, stream, static_cast<const uint32_t*>(d_compact), nnz, d_mask, d_prefix, alpha,
+                               reinterpret_cast<u32x4*>(d_weights), n);
+        else
+            hipLaunchKernelGGL((update_tile_kernel<uint16_t, kPackU>), dim3(div_up(tiles, kPackWaves)), dim3(kPackBlock),
+                               0, stream, static_cast<const uint16_t*>(d_compact), nnz, d_mask, d_prefix, alpha,
+                               reinterpret_cast<u32x4*>(d_weights), n);
+    } else {
+        const uint32_t blocks = div_up(n, kBlock);
+        if (dtype == 0)
+            hipLaunchKernelGGL((update_scalar_kernel<uint32_t>), dim3(blocks), dim3(kBlock), 0, stream,
+                               static_cast<const uint32_t*>(d_compact), nnz, d_mask, d_prefix, alpha, d_weights, n);
+        else
+            hipLaunchKernelGGL((update_scalar_kernel<uint16_t>), dim3(blocks), dim3(kBlock), 0, stream,
+                               static_cast<const uint16_t*>(d_compact), nnz, d_mask, d_prefix, alpha, d_weights, n);
     }
     return hipGetLastError();
 }
