@@ -81,7 +81,9 @@ uint32_t elem_size(pac_dtype dt) { return dt == PAC_F32 ? 4u : 2u; }
 
 // Stride of the sampled histogram pass over one prune scope: scopes below 8M elements are counted
 // in full; larger ones keep at least about 4M sampled elements, at most one 16384-element tile in 16.
+// 0 marks a small scope.
 uint32_t sample_stride(uint64_t len) {
+    if (len <= pac::kSmallScope) return 0;   // small scope: resolved by one workgroup, outside the histogram passes
     uint32_t stride = 1;
     while (stride < pac::kMaxSampleStride && len / (2ull * stride) >= (1ull << 22)) stride *= 2;
     return stride;
@@ -197,6 +199,13 @@ pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_
         }
     }
     if (ok) {
+        hipError_t r = pac::prepare_mask_kernels();
+        if (r != hipSuccess) {
+            ok = false;
+            code = fail(nullptr, PAC_ERR_HIP, "pac_create: kernel attributes: %s", hipGetErrorString(r));
+        }
+    }
+    if (ok) {
         // The histograms are all-zero between calls: the kernels that read them clear them.
         hipError_t r = hipMemset(s.hist0, 0, hist0_bytes);
         if (r == hipSuccess) r = hipMemset(s.hist1, 0, hist1_bytes);
@@ -262,12 +271,14 @@ pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n, cons
     // Keep counts: host arithmetic, so the total is known without waiting for the device.
     std::vector<pac::SegDesc> table(nseg);
     uint64_t total = 0, sampled = 0;
+    uint32_t max_small = 0;   // longest small scope of the table
     for (uint32_t s = 0; s < nseg; ++s) {
         const uint64_t b = h_seg_offsets[s], e = h_seg_offsets[s + 1];
         const uint64_t k = pac_keep_count(e - b, h_sparsity[s]);
         table[s] = pac::SegDesc{(uint32_t)b, (uint32_t)e, (uint32_t)k, sample_stride(e - b)};
         total += k;
-        sampled += (e - b) / table[s].stride;
+        if (table[s].stride != 0) sampled += (e - b) / table[s].stride;
+        else if (e - b > max_small) max_small = (uint32_t)(e - b);
     }
     if (h_nnz_out) *h_nnz_out = total;
     if (n == 0) return PAC_OK;
@@ -300,7 +311,7 @@ pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n, cons
         ctx->table_valid = true;
     }
 
-    hipError_t r = pac::launch_build_mask(ctx->scratch, d_weights, (uint32_t)n, nseg, sampled,
+    hipError_t r = pac::launch_build_mask(ctx->scratch, d_weights, (uint32_t)n, nseg, sampled, max_small,
                                           reinterpret_cast<unsigned long long*>(d_mask), d_prefix, ctx->num_cu, stream);
     if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_build_mask: launch: %s", hipGetErrorString(r));
     return PAC_OK;

@@ -28,7 +28,9 @@ struct SegDesc {
     uint32_t begin;    // first flat element
     uint32_t end;      // one past the last flat element
     uint32_t k;        // keep count
-    uint32_t stride;   // the first histogram pass visits one tile in `stride` (power of two; 1 = every tile)
+    uint32_t stride;   // the first histogram pass visits one tile in `stride` (power of two; 1 = every tile);
+                       // 0 marks a small scope (at most kSmallScope elements), which takes no part in the
+                       // histogram passes: one workgroup selects and writes its mask bits from LDS
 };
 
 // Selection state of one prune scope, device only.
@@ -43,16 +45,17 @@ struct SegState {
     uint32_t bin1;             // digit 1 of the k-th element
     uint32_t cnt1;             // undecided elements with that digit
     uint32_t krem1;            // rank of the k-th element among those
-    uint32_t in_place;         // small scope: its undecided elements are not listed, `final` and `fixup`
-                               // walk its weights (cheap, and keeps all-tie vectors out of the lists)
     uint32_t heavy;            // too many undecided elements share digit 1 for `final`'s LDS list:
                                // `final` walks this scope's weights
-    uint32_t pad;
+    uint32_t pad[2];
 };
 
 constexpr uint32_t kMaxSampleStride = 16;  // largest SegDesc::stride (power of two)
 
-constexpr uint32_t kSmallScope = 65536;   // scopes up to this many elements are resolved in place
+// Scopes of up to this many elements (norm and bias vectors, small kernels) are resolved by one
+// workgroup each with the keys held in LDS: exact whatever the ties, and no per-scope traffic in
+// the streaming passes.
+constexpr uint32_t kSmallScope = 32768;
 
 // The candidate list is split into regions with one fill counter each: an atomic on one address
 // costs about 10 ns and is serialised, so the appends of a call are spread over several addresses
@@ -97,9 +100,12 @@ struct MaskScratch {
 // Launchers (defined in pac_mask.hip / pac_pack.hip).  All enqueue on `stream` and return the
 // first launch error.
 // `sampled_elems`: elements the first histogram pass visits (sum over scopes of length / stride).
+// `max_small`: length of the longest small scope in the table (0 = none).
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
-                             uint64_t sampled_elems, unsigned long long* d_mask, uint32_t* d_prefix, int num_cu,
-                             hipStream_t stream);
+                             uint64_t sampled_elems, uint32_t max_small, unsigned long long* d_mask,
+                             uint32_t* d_prefix, int num_cu, hipStream_t stream);
+// Raises the small-scope kernel's LDS limit; once per device, before the first launch.
+hipError_t prepare_mask_kernels();
 
 // prefix[j] = set bits in words < j of any mask of at most the context's max_elems bits;
 // *d_total_out (device, may be null) receives the number of set bits.  Uses the context's scan scratch.

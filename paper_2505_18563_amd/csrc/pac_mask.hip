@@ -171,15 +171,16 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
         if (cur == kNone || a < cur_begin || a >= cur_end) s = find_seg(seg, nseg, a);
         const uint32_t s_end = s == cur ? cur_end : seg[s].end;
         if (s_end >= b) {
-            const uint32_t stride = pass != 0 ? 1u : (s == cur ? cur_stride : seg[s].stride);
+            const uint32_t raw_stride = s == cur ? cur_stride : seg[s].stride;
+            if (raw_stride == 0) continue;              // small scope: not part of the histogram passes
             if (s != cur) {
                 if (cur != kNone) flush_hist0(lds, hist0 + (size_t)cur * kDigit0Bins);
                 cur = s;
                 cur_begin = seg[s].begin;
                 cur_end = s_end;
-                cur_stride = stride;
+                cur_stride = raw_stride;
             }
-            if (!tile_sampled(t, stride)) continue;
+            if (pass == 0 && !tile_sampled(t, raw_stride)) continue;
             if (VEC && b - a == kHistTile) {
                 const u32x4* p = reinterpret_cast<const u32x4*>(w + a) + threadIdx.x;
                 u32x4 v[kHistLoads];
@@ -197,18 +198,27 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
                     atomicAdd(&lds[digit0_of(key_of_bits(__float_as_uint(w[i])))], 1u);
             }
         } else {
-            // The tile crosses scope boundaries: element by element into the global histograms,
-            // each element under its own scope's sampling rule.
-            for (u64 i0 = a; i0 < b; i0 += kHistBlock) {   // same trip count in every lane
-                const u64 i = i0 + threadIdx.x;
-                bool count = i < b;
-                uint32_t idx = 0;
-                if (count) {
-                    const uint32_t si = find_seg(seg, nseg, (uint32_t)i);
-                    count = pass != 0 || tile_sampled(t, seg[si].stride);
-                    idx = si * kDigit0Bins + digit0_of(key_of_bits(__float_as_uint(w[i])));
+            // The tile crosses scope boundaries: one sub-range per scope, each under its own scope's
+            // sampling rule, through the LDS histogram like a whole tile.
+            uint32_t sc = s, pos = a;
+            while (pos < b) {                           // the last scope ends at n >= b
+                const uint32_t sb = seg[sc].begin, se = seg[sc].end, sstride = seg[sc].stride;
+                if (se > pos) {
+                    const uint32_t upto = min(se, b);
+                    if (sstride != 0 && (pass != 0 || tile_sampled(t, sstride))) {
+                        if (sc != cur) {
+                            if (cur != kNone) flush_hist0(lds, hist0 + (size_t)cur * kDigit0Bins);
+                            cur = sc;
+                            cur_begin = sb;
+                            cur_end = se;
+                            cur_stride = sstride;
+                        }
+                        for (u64 i = (u64)pos + threadIdx.x; i < upto; i += kHistBlock)
+                            atomicAdd(&lds[digit0_of(key_of_bits(__float_as_uint(w[i])))], 1u);
+                    }
+                    pos = upto;
                 }
-                wave_aggregated_inc(hist0, idx, count);
+                ++sc;
             }
         }
     }
@@ -300,14 +310,17 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
     const uint32_t below = block_exclusive_scan<THREADS>(sum, wave_sums, counted);
     const uint32_t above = counted - below - sum;   // elements in bins owned by higher threads
 
-    if (k == 0 || k == n_s) {
-        // Nothing to resolve: keep nothing (hi above every key) or everything (hi = 0).
+    const bool small = seg[s].stride == 0;
+    if (k == 0 || k == n_s || small) {
+        // Nothing to resolve here: keep nothing (hi above every key) or everything (hi = 0).  A small
+        // scope is left all-zero by emit and written by its own workgroup afterwards.
+        const bool none = k == 0 || small;
         if (threadIdx.x == 0) {
-            st->cstar = k == 0 ? ~0ull : 0ull;
+            st->cstar = none ? ~0ull : 0ull;
             st->active = 0;
-            st->lo = st->hi = k == 0 ? kKeyEnd : 0u;
+            st->lo = st->hi = none ? kKeyEnd : 0u;
             st->sh1 = 0; st->exact = 1; st->krem0 = 0; st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
-            st->in_place = 1; st->heavy = 0;
+            st->heavy = 0;
         }
         return;
     }
@@ -366,12 +379,11 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
         st->exact = exact ? 1u : 0u;
         st->krem0 = exact ? k - sh_above_hi : 0u;
         st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
-        st->in_place = n_s <= kSmallScope ? 1u : 0u;
         st->heavy = 0;
         // undecided elements this scope will list (scaled up, with a margin, when sampled)
         u64 est = sh_in_range;
         if (!exact) est = (u64)((double)est * ((double)n_s / (double)counted) * 1.25) + 1024;
-        if (n_s > kSmallScope) atomicAdd(&glob->cand_total, est);
+        atomicAdd(&glob->cand_total, est);
     }
 }
 
@@ -592,7 +604,7 @@ __global__ __launch_bounds__(kEmitBlock, PAC_EXP_EMIT_WAVES) void emit_kernel(co
             s_lo = state[s0].lo;
             s_hi = state[s0].hi;
             s_sh1 = state[s0].sh1;
-            s_list = listing && !state[s0].in_place;
+            s_list = listing;
         }
 
         if (single && whole) {
@@ -667,7 +679,7 @@ __global__ __launch_bounds__(kEmitBlock, PAC_EXP_EMIT_WAVES) void emit_kernel(co
                         kept = key >= hi;
                         undecided = !kept && key >= lo;
                         if (undecided) d1 = (key - lo) >> state[si].sh1;
-                        append = undecided && listing && !state[si].in_place;
+                        append = undecided && listing;
                         if (kept) nib |= 1u << e;
                         kept = kept && !state[si].exact;   // only sampled scopes need the count
                     }
@@ -801,7 +813,7 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
     const uint32_t begin = seg[s].begin, end = seg[s].end;
     if (threadIdx.x == 0) { found[0] = 0; found[1] = 0; gathered = 0; }
     __syncthreads();
-    const bool from_list = !glob->overflow && !glob->match_overflow && !st->in_place && !st->heavy;
+    const bool from_list = !glob->overflow && !glob->match_overflow && !st->heavy;
     if (from_list) {
         // Matches of this scope: thread t looks through the slots of compact2's workgroup t.
         static_assert(kFinalBlock == (int)kMatchBlocks, "one thread per compact2 workgroup");
@@ -821,6 +833,104 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
         final_levels<false>(nullptr, 0, w, begin, end, tail_bits, prefix, krem, hist, wave_sums, found);
     }
     if (threadIdx.x == 0) st->cstar = prefix;
+}
+
+// -------------------------------------------------------------------------------- small scopes
+// One workgroup resolves one small scope completely: keys into LDS, a radix select over the 31 key
+// bits (8-bit digits, counted with run-length aggregation so that a vector of equal values costs
+// one LDS atomic per thread and level), then the tie rule by position - among the elements equal
+// to the threshold key the first r in flat order are kept - with one ballot per mask word, a wave
+// owning the 64 elements of one word.  Words that lie inside the scope are stored (emit left them
+// zero), the two words shared with neighbouring scopes are OR-ed.
+constexpr int kSmallBlock = 1024;
+constexpr uint32_t kSmallWords = kSmallScope / 64 + 2;    // mask words one small scope can touch
+
+__global__ __launch_bounds__(kSmallBlock) void small_scope_kernel(const float* __restrict__ w,
+                                                                  const SegDesc* __restrict__ seg,
+                                                                  u64* __restrict__ mask) {
+    extern __shared__ uint32_t keys[];                     // [scope length]
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t wave_sums[kSmallBlock / 64];
+    __shared__ uint32_t found[2];
+    __shared__ uint32_t eq_before[kSmallWords];
+    const SegDesc d = seg[blockIdx.x];
+    if (d.stride != 0) return;                             // not a small scope
+    const uint32_t begin = d.begin, end = d.end, len = end - begin, k = d.k;
+    if (len == 0 || k == 0) return;                        // nothing kept: emit wrote the zeros
+    for (uint32_t j = threadIdx.x; j < len; j += kSmallBlock) keys[j] = key_of_bits(__float_as_uint(w[begin + j]));
+    if (threadIdx.x == 0) { found[0] = 0; found[1] = 0; }
+    __syncthreads();
+
+    // key of the k-th largest element, and its rank r among the elements with that key
+    uint32_t prefix = 0, krem = k, resolved_above = 31;
+    while (resolved_above > 0) {
+        const uint32_t width = resolved_above >= 8 ? 8u : resolved_above;
+        const uint32_t shift = resolved_above - width;
+        if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+        __syncthreads();
+        uint32_t run_digit = 0, run = 0;
+        for (uint32_t j = threadIdx.x; j < len; j += kSmallBlock) {
+            const uint32_t key = keys[j];
+            if (((key ^ prefix) >> resolved_above) == 0) {
+                const uint32_t digit = (key >> shift) & ((1u << width) - 1u);
+                if (run != 0 && digit != run_digit) {
+                    atomicAdd(&hist[run_digit], run);
+                    run = 0;
+                }
+                run_digit = digit;
+                ++run;
+            }
+        }
+        if (run != 0) atomicAdd(&hist[run_digit], run);
+        __syncthreads();
+        const uint32_t v = threadIdx.x < 256 ? hist[threadIdx.x] : 0u;
+        uint32_t total;
+        const uint32_t below = block_exclusive_scan<kSmallBlock>(v, wave_sums, total);
+        const uint32_t above = total - below - v;
+        if (v != 0 && above < krem && krem <= above + v) {
+            found[0] = threadIdx.x;
+            found[1] = krem - above;
+        }
+        __syncthreads();
+        prefix |= found[0] << shift;
+        krem = found[1];
+        resolved_above = shift;
+        __syncthreads();
+    }
+    const uint32_t thr = prefix, r = krem;
+
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+    const uint32_t base0 = begin & ~63u;                   // first element of the first word touched
+    const uint32_t words = (uint32_t)(((u64)end - base0 + 63) >> 6);
+    for (uint32_t wd = wave; wd < words; wd += kSmallBlock / 64) {
+        const u64 g = (u64)base0 + wd * 64u + lane;
+        const bool eq = g >= begin && g < end && keys[g - begin] == thr;
+        const u64 m = __ballot(eq);
+        if (lane == 0) eq_before[wd] = (uint32_t)__popcll(m);
+    }
+    __syncthreads();
+    {
+        // exclusive scan over the words' counts of threshold-equal elements
+        uint32_t total;
+        const uint32_t v = threadIdx.x < words ? eq_before[threadIdx.x] : 0u;
+        const uint32_t ex = block_exclusive_scan<kSmallBlock>(v, wave_sums, total);
+        if (threadIdx.x < words) eq_before[threadIdx.x] = ex;
+        __syncthreads();
+    }
+    for (uint32_t wd = wave; wd < words; wd += kSmallBlock / 64) {
+        const u64 g0 = (u64)base0 + wd * 64u;
+        const u64 g = g0 + lane;
+        const bool valid = g >= begin && g < end;
+        const uint32_t key = valid ? keys[g - begin] : 0u;
+        const bool eq = valid && key == thr;
+        const u64 eqm = __ballot(eq);
+        const bool keep = valid && (key > thr || (eq && eq_before[wd] + lanes_below(eqm) < r));
+        const u64 bits = __ballot(keep);
+        if (lane == 0 && bits != 0) {
+            if (g0 >= begin && g0 + 64 <= end) mask[g0 >> 6] = bits;
+            else atomicOr(&mask[g0 >> 6], bits);
+        }
+    }
 }
 
 // -------------------------------------------------------------------------------------- fixup
@@ -845,18 +955,6 @@ __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restri
             const uint32_t i = index_of(c);
             const uint32_t s = nseg > 1 ? find_seg(seg, nseg, i) : 0u;
             if (c >= state[s].cstar) atomicOr(&mask[i >> 6], 1ull << (i & 63u));
-        }
-        // Scopes resolved in place have no list entries: walk their weights, one workgroup per scope.
-        for (uint32_t s = blockIdx.y * gridDim.x + blockIdx.x; s < nseg; s += gridDim.x * gridDim.y) {
-            const SegState* st = state + s;
-            if (!st->active || !st->in_place) continue;
-            const uint32_t lo = st->lo, hi = st->hi;
-            const u64 cstar = st->cstar;
-            for (u64 i = (u64)seg[s].begin + threadIdx.x; i < seg[s].end; i += kListBlock) {
-                const uint32_t key = key_of_bits(__float_as_uint(w[i]));
-                if (key >= lo && key < hi && composite_of(key, (uint32_t)i) >= cstar)
-                    atomicOr(&mask[i >> 6], 1ull << (i & 63u));
-            }
         }
     } else {
         // Lists not in use: walk the weights.
@@ -1035,9 +1133,14 @@ uint32_t resident_blocks(K kernel, int block, int num_cu, uint32_t fallback_per_
 
 }  // namespace
 
+hipError_t prepare_mask_kernels() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(small_scope_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kSmallScope * sizeof(uint32_t)));
+}
+
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
-                             uint64_t sampled_elems, unsigned long long* d_mask, uint32_t* d_prefix, int num_cu,
-                             hipStream_t stream) {
+                             uint64_t sampled_elems, uint32_t max_small, unsigned long long* d_mask,
+                             uint32_t* d_prefix, int num_cu, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     const uint32_t words = div_up_u64(n, 64);
     const bool aligned = (reinterpret_cast<uintptr_t>(d_weights) & 15u) == 0;
@@ -1075,6 +1178,10 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
         hipLaunchKernelGGL(select1_kernel, dim3(nseg), dim3(kDigit1Bins / 16), 0, stream, s.seg, s.state, s.hist1,
                            s.kept_above, s.glob, pass);
     }
+
+    if (max_small != 0)   // after the last emit: it overwrites the small scopes' all-zero words
+        hipLaunchKernelGGL(small_scope_kernel, dim3(nseg), dim3(kSmallBlock), (size_t)max_small * sizeof(uint32_t),
+                           stream, d_weights, s.seg, d_mask);
 
     const uint32_t list_blocks = 256;   // per candidate region
     static_assert(kListBlock == 256, "compact2 runs 4 waves per workgroup");

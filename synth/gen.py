@@ -15,6 +15,10 @@ elsewhere copies the bytes.  Recipes:
             bf16 (nearest even), global s=0.9, W=16
   config 5  1.3B decoder shapes, same weight recipe, fp32 grads N(0, 1e-4^2), every
             tensor its own scope, s taken from (0.5, 0.8, 0.95) by step, W=8
+  configs 6-8  the paper's own evaluation models with a 100-way classifier (Sec. IV-A: VGG19,
+            ResNet152, ViT-Base-16 on CIFAR-100), at its default pruning ratio 0.5 and its 8 workers
+            (Sec. IV-C), fp32: the two convolutional nets with config 2's recipe, the transformer
+            with config 5's; every tensor its own prune scope
 """
 from __future__ import annotations
 
@@ -32,7 +36,12 @@ CONFIGS: Dict[int, dict] = {
     3: dict(name="bert-base-shaped", scope="global", sparsity=(0.7,), workers=8, dtype="f32"),
     4: dict(name="gpt2-medium-shaped", scope="global", sparsity=(0.9,), workers=16, dtype="bf16"),
     5: dict(name="decoder-1.3b-shaped", scope="per-layer", sparsity=(0.5, 0.8, 0.95), workers=8, dtype="f32"),
+    6: dict(name="vgg19-cifar100-shaped", scope="per-layer", sparsity=(0.5,), workers=8, dtype="f32"),
+    7: dict(name="resnet152-cifar100-shaped", scope="per-layer", sparsity=(0.5,), workers=8, dtype="f32"),
+    8: dict(name="vit-base-16-cifar100-shaped", scope="per-layer", sparsity=(0.5,), workers=8, dtype="f32"),
 }
+
+CONV_NETS = (2, 6, 7)   # He-normal weights, fan-in scaled gradients
 
 SEED_BASE = 0x5AC70000
 
@@ -62,7 +71,7 @@ class Workload:
 
 def _reduced_specs(config_id: int) -> List[TensorSpec]:
     """Same tensor kinds and order, fewer layers and smaller odd-sized dimensions."""
-    if config_id in (1, 2):
+    if config_id in (1, 2, 6, 7, 8):
         return config_shapes(config_id)
     if config_id == 3:
         from .shapes import _linear, _ln  # local: builds a 2-layer BERT-like list
@@ -92,7 +101,7 @@ def _fill_weights(flat: torch.Tensor, specs: List[TensorSpec], config_id: int, g
     if config_id == 1:
         flat.normal_(0.0, 1.0 / 32.0, generator=gen)
         return
-    if config_id != 2:
+    if config_id not in CONV_NETS:
         flat.normal_(0.0, 0.02, generator=gen)
     for s in specs:
         view = flat[off:off + s.numel]
@@ -100,7 +109,7 @@ def _fill_weights(flat: torch.Tensor, specs: List[TensorSpec], config_id: int, g
             view.fill_(1.0)
         elif s.kind in ("beta", "bias"):
             view.zero_()
-        elif config_id == 2:
+        elif config_id in CONV_NETS:
             view.normal_(0.0, math.sqrt(2.0 / s.fan_in), generator=gen)
         off += s.numel
 
@@ -123,7 +132,7 @@ def _make_grad(specs: List[TensorSpec], n: int, config_id: int, dtype: str, devi
         g = torch.empty(n, dtype=torch.float32, device=device)
         if config_id == 1:
             g.normal_(0.0, 1e-3, generator=gen)
-        elif config_id == 2:
+        elif config_id in CONV_NETS:
             off = 0
             for s in specs:
                 sigma = 1e-3 * math.sqrt(576.0 / s.fan_in) if s.fan_in else 1e-3

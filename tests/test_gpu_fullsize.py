@@ -79,3 +79,10 @@ def test_full_config4_gpt2_medium_shaped_bf16_w16():
 def test_full_config5_decoder_1p3b_per_layer_schedule_two_workers():
     """1,315,723,264 elements, 292 prune scopes (the large ones sampled), every sparsity of the schedule."""
     run_full(5, workers=2, steps=(0, 1, 2))
+
+
+@pytest.mark.parametrize("config_id", [6, 7, 8])
+def test_full_paper_models_pruning_ratio_half_two_workers(config_id):
+    """The paper's own evaluation models (VGG19, ResNet152, ViT-Base-16 with a 100-way classifier) at its
+    default pruning ratio 0.5, every tensor its own prune scope; 2 of the 8 workers to bound host time."""
+    run_full(config_id, workers=2)

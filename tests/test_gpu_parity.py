@@ -99,7 +99,7 @@ def weights_of(kind: str, n: int, rng) -> np.ndarray:
 
 # ------------------------------------------------------------------------------------ build_mask
 @pytest.mark.parametrize("kind", ["gauss", "ties", "equal", "zeros_half", "special", "narrow"])
-@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000, 4097, 16384, 16385, 100003, (1 << 20) + 77])
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000, 4097, 16384, 16385, 32767, 32768, 32769, 65537, 100003, (1 << 20) + 77])
 def test_build_mask_global(ctx, kind, n):
     rng = np.random.default_rng(sum(map(ord, kind)) * 131 + n)
     w = weights_of(kind, n, rng)
@@ -116,6 +116,20 @@ def test_build_mask_segmented_ragged(ctx):
         w = weights_of(kind, n, rng)
         sp = rng.choice([0.0, 0.3, 0.5, 0.9, 0.95, 1.0], size=len(sizes))
         check_mask(ctx, w, off, sp, f"ragged {kind}")
+
+
+def test_build_mask_small_and_large_scopes_interleaved(ctx):
+    """Scopes on both sides of the small-scope limit (32768 elements), none aligned to a mask word, so that
+    every boundary word is shared between a scope resolved by its own workgroup and a streamed one."""
+    rng = np.random.default_rng(24)
+    sizes = [33001, 17, 32768, 40003, 1, 32769, 255, 100001, 31999, 70007, 3, 64, 65, 50001]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(off[-1])
+    for kind in ("gauss", "ties", "equal", "special", "narrow"):
+        w = weights_of(kind, n, rng)
+        for trial in range(2):
+            sp = rng.choice([0.0, 0.25, 0.5, 0.9, 0.99, 1.0], size=len(sizes))
+            check_mask(ctx, w, off, sp, f"interleaved {kind} #{trial}")
 
 
 def test_build_mask_many_small_segments(ctx):

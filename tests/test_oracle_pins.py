@@ -79,6 +79,13 @@ def test_flat_sizes_golden():
         assert flat_size(specs) == int(n)
 
 
+def test_paper_model_shapes_reach_the_published_parameter_counts():
+    from synth.shapes import _resnet152, _vgg19, _vit_base_16
+    assert flat_size(_vgg19(1000)) == 143667240
+    assert flat_size(_resnet152(1000)) == 60192808
+    assert flat_size(_vit_base_16(1000)) == 86567656
+
+
 # ----------------------------------------------------------------------------- kept set
 @pytest.mark.parametrize("n", [1, 2, 7, 63, 64, 65, 130, 257, 700])
 def test_mask_equals_brute_force_with_heavy_ties(n):
