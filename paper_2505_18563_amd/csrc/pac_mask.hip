@@ -289,6 +289,18 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
     const uint32_t k = seg[s].k;
     const uint32_t n_s = seg[s].end - seg[s].begin;
     SegState* st = state + s;
+    if (seg[s].stride == 0) {
+        // A small scope takes no part in the streaming passes: emit leaves it all-zero (no key reaches
+        // hi) and its own workgroup writes its bits afterwards.  Its histogram rows stay zero.
+        if (threadIdx.x == 0) {
+            st->cstar = ~0ull;
+            st->active = 0;
+            st->lo = st->hi = kKeyEnd;
+            st->sh1 = 0; st->exact = 1; st->krem0 = 0; st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
+            st->heavy = 0;
+        }
+        return;
+    }
 
     // this scope's kept counters start from zero
     for (uint32_t j = threadIdx.x; j < kCandRegions * kFillStride; j += THREADS)
@@ -310,11 +322,9 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
     const uint32_t below = block_exclusive_scan<THREADS>(sum, wave_sums, counted);
     const uint32_t above = counted - below - sum;   // elements in bins owned by higher threads
 
-    const bool small = seg[s].stride == 0;
-    if (k == 0 || k == n_s || small) {
-        // Nothing to resolve here: keep nothing (hi above every key) or everything (hi = 0).  A small
-        // scope is left all-zero by emit and written by its own workgroup afterwards.
-        const bool none = k == 0 || small;
+    if (k == 0 || k == n_s) {
+        // Nothing to resolve: keep nothing (hi above every key) or everything (hi = 0).
+        const bool none = k == 0;
         if (threadIdx.x == 0) {
             st->cstar = none ? ~0ull : 0ull;
             st->active = 0;
@@ -660,8 +670,11 @@ __global__ __launch_bounds__(kEmitBlock, PAC_EXP_EMIT_WAVES) void emit_kernel(co
                 }
             }
         } else {
-            // Plain path: every lane handles 4 consecutive elements with its own bounds and scope lookups;
-            // counters are bumped once per wave and distinct target.
+            // Plain path: every lane handles 4 consecutive elements with its own bounds and scopes.  A
+            // lane's elements come in ascending order, so its scope only moves forward from the scope of
+            // the tile's first element; counters are bumped once per wave and distinct target.
+            uint32_t sc = s0, sc_end = s0_end;
+            uint32_t lo = state[s0].lo, hi = state[s0].hi, sh1 = state[s0].sh1, exact = state[s0].exact;
 #pragma unroll 1
             for (uint32_t u = 0; u < kEmitLoads; ++u) {
                 const u64 first = wave_first + u * 256u;
@@ -671,20 +684,23 @@ __global__ __launch_bounds__(kEmitBlock, PAC_EXP_EMIT_WAVES) void emit_kernel(co
                     const u64 i64 = first + lane * 4u + e;
                     const uint32_t i = (uint32_t)i64;
                     bool kept = false, undecided = false, append = false;
-                    uint32_t key = 0, si = 0, d1 = 0;
+                    uint32_t key = 0, d1 = 0;
                     if (i64 < n) {
+                        while (i >= sc_end) {           // ends: the last scope ends at n > i
+                            ++sc;
+                            sc_end = seg[sc].end;
+                            if (i < sc_end) { lo = state[sc].lo; hi = state[sc].hi; sh1 = state[sc].sh1; exact = state[sc].exact; }
+                        }
                         key = key_of_bits(__float_as_uint(w[i]));
-                        si = find_seg(seg, nseg, i);
-                        const uint32_t lo = state[si].lo, hi = state[si].hi;
                         kept = key >= hi;
                         undecided = !kept && key >= lo;
-                        if (undecided) d1 = (key - lo) >> state[si].sh1;
+                        if (undecided) d1 = (key - lo) >> sh1;
                         append = undecided && listing;
                         if (kept) nib |= 1u << e;
-                        kept = kept && !state[si].exact;   // only sampled scopes need the count
+                        kept = kept && !exact;          // only sampled scopes need the count
                     }
-                    wave_aggregated_inc(kept_above, (si * kCandRegions + region) * kFillStride, kept);
-                    wave_aggregated_inc(hist1, si * kDigit1Bins + d1, undecided);
+                    wave_aggregated_inc(kept_above, (sc * kCandRegions + region) * kFillStride, kept);
+                    wave_aggregated_inc(hist1, sc * kDigit1Bins + d1, undecided);
                     const u64 am = __ballot(append);
                     if (am != 0) {
                         uint32_t g = 0;
@@ -837,36 +853,43 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
 
 // -------------------------------------------------------------------------------- small scopes
 // One workgroup resolves one small scope completely: keys into LDS, a radix select over the 31 key
-// bits (8-bit digits, counted with run-length aggregation so that a vector of equal values costs
-// one LDS atomic per thread and level), then the tie rule by position - among the elements equal
+// bits, then the tie rule by position - among the elements equal
 // to the threshold key the first r in flat order are kept - with one ballot per mask word, a wave
 // owning the 64 elements of one word.  Words that lie inside the scope are stored (emit left them
 // zero), the two words shared with neighbouring scopes are OR-ed.
-constexpr int kSmallBlock = 1024;
-constexpr uint32_t kSmallWords = kSmallScope / 64 + 2;    // mask words one small scope can touch
-
+// Two size classes, so that the many very short vectors of a model run with small workgroups and
+// little LDS, many to a compute unit: scopes of up to kTinyScope elements with 256 threads, the rest
+// with 1024.
+template <int kSmallBlock, uint32_t kMaxLen>
 __global__ __launch_bounds__(kSmallBlock) void small_scope_kernel(const float* __restrict__ w,
                                                                   const SegDesc* __restrict__ seg,
-                                                                  u64* __restrict__ mask) {
+                                                                  u64* __restrict__ mask, uint32_t min_len) {
+    constexpr uint32_t kSmallWords = kMaxLen / 64 + 2;     // mask words one scope of this class can touch
+    static_assert(kSmallWords <= (uint32_t)kSmallBlock, "one thread per word in the scan over words");
     extern __shared__ uint32_t keys[];                     // [scope length]
-    __shared__ uint32_t hist[256];
+    __shared__ uint32_t hist[2048];
     __shared__ uint32_t wave_sums[kSmallBlock / 64];
     __shared__ uint32_t found[2];
     __shared__ uint32_t eq_before[kSmallWords];
     const SegDesc d = seg[blockIdx.x];
     if (d.stride != 0) return;                             // not a small scope
     const uint32_t begin = d.begin, end = d.end, len = end - begin, k = d.k;
+    if (len < min_len || len > kMaxLen) return;            // the other size class
     if (len == 0 || k == 0) return;                        // nothing kept: emit wrote the zeros
     for (uint32_t j = threadIdx.x; j < len; j += kSmallBlock) keys[j] = key_of_bits(__float_as_uint(w[begin + j]));
     if (threadIdx.x == 0) { found[0] = 0; found[1] = 0; }
     __syncthreads();
 
-    // key of the k-th largest element, and its rank r among the elements with that key
+    // key of the k-th largest element, and its rank r among the elements with that key: digits of
+    // 11, 10 and 10 bits, most significant first.  (The leading byte of a float key is its exponent,
+    // which takes only a handful of values in a weight tensor and would serialise the LDS atomics
+    // on a few bins; three more bits spread the counts.)  A thread adds a run of equal digits at once.
+    constexpr uint32_t kBins = 2048, kPer = kBins / kSmallBlock;
     uint32_t prefix = 0, krem = k, resolved_above = 31;
     while (resolved_above > 0) {
-        const uint32_t width = resolved_above >= 8 ? 8u : resolved_above;
+        const uint32_t width = resolved_above == 31 ? 11u : 10u;
         const uint32_t shift = resolved_above - width;
-        if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+        for (uint32_t b = threadIdx.x; b < kBins; b += kSmallBlock) hist[b] = 0;
         __syncthreads();
         uint32_t run_digit = 0, run = 0;
         for (uint32_t j = threadIdx.x; j < len; j += kSmallBlock) {
@@ -883,13 +906,22 @@ __global__ __launch_bounds__(kSmallBlock) void small_scope_kernel(const float* _
         }
         if (run != 0) atomicAdd(&hist[run_digit], run);
         __syncthreads();
-        const uint32_t v = threadIdx.x < 256 ? hist[threadIdx.x] : 0u;
+        // thread t owns bins [t * kPer, (t + 1) * kPer); walk from the highest bin down
+        uint32_t loc[kPer], v = 0;
+#pragma unroll
+        for (uint32_t q = 0; q < kPer; ++q) { loc[q] = hist[threadIdx.x * kPer + q]; v += loc[q]; }
         uint32_t total;
         const uint32_t below = block_exclusive_scan<kSmallBlock>(v, wave_sums, total);
-        const uint32_t above = total - below - v;
+        uint32_t above = total - below - v;
         if (v != 0 && above < krem && krem <= above + v) {
-            found[0] = threadIdx.x;
-            found[1] = krem - above;
+#pragma unroll
+            for (int q = (int)kPer - 1; q >= 0; --q) {
+                if (above < krem && krem <= above + loc[q]) {
+                    found[0] = threadIdx.x * kPer + (uint32_t)q;
+                    found[1] = krem - above;
+                }
+                above += loc[q];
+            }
         }
         __syncthreads();
         prefix |= found[0] << shift;
@@ -1134,13 +1166,13 @@ uint32_t resident_blocks(K kernel, int block, int num_cu, uint32_t fallback_per_
 }  // namespace
 
 hipError_t prepare_mask_kernels() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(small_scope_kernel),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(small_scope_kernel<1024, kSmallScope>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kSmallScope * sizeof(uint32_t)));
 }
 
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
-                             uint64_t sampled_elems, uint32_t max_small, unsigned long long* d_mask,
-                             uint32_t* d_prefix, int num_cu, hipStream_t stream) {
+                             uint64_t sampled_elems, uint32_t max_tiny, uint32_t max_small,
+                             unsigned long long* d_mask, uint32_t* d_prefix, int num_cu, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     const uint32_t words = div_up_u64(n, 64);
     const bool aligned = (reinterpret_cast<uintptr_t>(d_weights) & 15u) == 0;
@@ -1179,9 +1211,13 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
                            s.kept_above, s.glob, pass);
     }
 
-    if (max_small != 0)   // after the last emit: it overwrites the small scopes' all-zero words
-        hipLaunchKernelGGL(small_scope_kernel, dim3(nseg), dim3(kSmallBlock), (size_t)max_small * sizeof(uint32_t),
-                           stream, d_weights, s.seg, d_mask);
+    // after the last emit: these overwrite the small scopes' all-zero words
+    if (max_tiny != 0)
+        hipLaunchKernelGGL((small_scope_kernel<256, kTinyScope>), dim3(nseg), dim3(256),
+                           (size_t)max_tiny * sizeof(uint32_t), stream, d_weights, s.seg, d_mask, 0u);
+    if (max_small > kTinyScope)
+        hipLaunchKernelGGL((small_scope_kernel<1024, kSmallScope>), dim3(nseg), dim3(1024),
+                           (size_t)max_small * sizeof(uint32_t), stream, d_weights, s.seg, d_mask, kTinyScope + 1u);
 
     const uint32_t list_blocks = 256;   // per candidate region
     static_assert(kListBlock == 256, "compact2 runs 4 waves per workgroup");
