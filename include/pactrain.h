@@ -164,10 +164,10 @@ pac_status pac_decompress_update(pac_ctx* ctx, const void* d_reduced, pac_dtype 
                                  const uint64_t* d_mask, const uint32_t* d_prefix, float alpha,
                                  float* d_weights, uint64_t n, void* hip_stream);
 
-/* Test hook: lower the capacity of the candidate list pac_build_mask uses between its selection
- * passes (elements; clamped to what pac_create allocated).  Scopes whose candidates do not fit take
- * the slower in-place selection; results are identical.  Exists so that tests can reach that branch
- * with small inputs. */
+/* Test hook: lower the number of undecided elements pac_build_mask lists between its selection passes
+ * (elements in total; each 4096-element tile gets its share, at most 127).  Tiles whose undecided
+ * elements do not fit are re-read from the weights by the later passes; results are identical.
+ * Exists so that tests can reach that branch with small inputs. */
 pac_status pac_debug_set_candidate_capacity(pac_ctx* ctx, uint64_t capacity);
 
 #ifdef __cplusplus

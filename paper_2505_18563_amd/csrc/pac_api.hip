@@ -26,7 +26,6 @@ struct pac_ctx {
     uint64_t max_elems = 0;
     uint32_t max_segments = 0;
     pac::MaskScratch scratch{};
-    uint32_t cand_cap_alloc = 0;
     // segment table staging
     pac::SegDesc* h_ring[kRing] = {nullptr, nullptr, nullptr, nullptr};
     hipEvent_t ring_event[kRing] = {nullptr, nullptr, nullptr, nullptr};
@@ -97,7 +96,8 @@ void free_scratch(pac_ctx* ctx) {
     (void)hipFree(s.hist1);
     (void)hipFree(s.kept_above);
     (void)hipFree(s.glob);
-    (void)hipFree(s.cand);
+    (void)hipFree(s.rec);
+    (void)hipFree(s.tile_scope);
     (void)hipFree(s.match);
     (void)hipFree(s.match_count);
     (void)hipFree(s.tile_state);
@@ -157,15 +157,9 @@ pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_
     }
     ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
-    // Candidate lists: one sixteenth of the elements is far above what continuous weight
-    // distributions produce (well under 1 %); tie-heavy scopes beyond it take the in-place path.
-    uint64_t cap = max_elems / 16;
-    if (cap < 65536) cap = 65536;
-    if (cap > max_elems) cap = max_elems;
-    ctx->cand_cap_alloc = (uint32_t)cap;
-
     pac::MaskScratch& s = ctx->scratch;
-    s.cand_cap = ctx->cand_cap_alloc;
+    s.cand_cap = ~0ull;   // every tile record may use all of its slots
+    const uint64_t emit_tiles = (max_elems + pac::kEmitTileElems - 1) / pac::kEmitTileElems;
     const uint64_t words = pac_mask_words(max_elems);
     const uint64_t scan_tiles = (words + kScanTileWords - 1) / kScanTileWords;
     const size_t hist0_bytes = (size_t)max_segments * pac::kDigit0Bins * sizeof(uint32_t);
@@ -184,9 +178,10 @@ pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_
     alloc((void**)&s.state, (size_t)max_segments * sizeof(pac::SegState));
     alloc((void**)&s.hist0, hist0_bytes);
     alloc((void**)&s.hist1, hist1_bytes);
-    alloc((void**)&s.kept_above, (size_t)max_segments * pac::kCandRegions * pac::kFillStride * sizeof(uint32_t));
+    alloc((void**)&s.kept_above, (size_t)max_segments * sizeof(uint32_t));
     alloc((void**)&s.glob, sizeof(pac::Globals));
-    alloc((void**)&s.cand, (size_t)cap * sizeof(unsigned long long));
+    alloc((void**)&s.rec, (size_t)emit_tiles * pac::kRecSlots * sizeof(unsigned long long));
+    alloc((void**)&s.tile_scope, (size_t)emit_tiles * sizeof(uint32_t));
     alloc((void**)&s.match, (size_t)pac::kMatchSlots * sizeof(unsigned long long));
     alloc((void**)&s.match_count, (size_t)pac::kMatchBlocks * sizeof(uint32_t));
     alloc((void**)&s.tile_state, (size_t)(scan_tiles + 1) * sizeof(unsigned long long));
@@ -237,8 +232,7 @@ pac_status pac_destroy(pac_ctx* ctx) {
 
 pac_status pac_debug_set_candidate_capacity(pac_ctx* ctx, uint64_t capacity) {
     if (!ctx) return PAC_ERR_ARG;
-    if (capacity > ctx->cand_cap_alloc) capacity = ctx->cand_cap_alloc;
-    ctx->scratch.cand_cap = (uint32_t)capacity;
+    ctx->scratch.cand_cap = capacity;
     return PAC_OK;
 }
 
@@ -315,7 +309,7 @@ pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n, cons
     }
 
     hipError_t r = pac::launch_build_mask(ctx->scratch, d_weights, (uint32_t)n, nseg, sampled, max_tiny, max_small,
-                                          reinterpret_cast<unsigned long long*>(d_mask), d_prefix, ctx->num_cu, stream);
+                                          !same, reinterpret_cast<unsigned long long*>(d_mask), d_prefix, ctx->num_cu, stream);
     if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_build_mask: launch: %s", hipGetErrorString(r));
     return PAC_OK;
 }

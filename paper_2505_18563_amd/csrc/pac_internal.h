@@ -57,28 +57,26 @@ constexpr uint32_t kMaxSampleStride = 16;  // largest SegDesc::stride (power of 
 // the streaming passes.
 constexpr uint32_t kSmallScope = 32768;
 
-// The candidate list is split into regions with one fill counter each: an atomic on one address
-// costs about 10 ns and is serialised, so the appends of a call are spread over several addresses
-// and batched (one atomic per staged flush).
-constexpr uint32_t kCandRegions = 16;
-constexpr uint32_t kFillStride = 64;   // uint32 slots between two fill counters: one 256-byte block each
+// emit leaves one record per tile of kEmitTileElems elements (room for 3 % of them; a bracket of a
+// few histogram bins holds about 1 %): kRecSlots 64-bit slots, slot 0 the
+// header (elements above the bracket << 32 | listed undecided elements), then their composites.
+// A header count of kRecWalk means "not listed": consumers walk the tile's weights.
+constexpr uint32_t kEmitTileElems = 4096;
+constexpr uint32_t kRecSlots = 128;
+constexpr uint32_t kRecWalk = 0xFFFFFFFFu;
 
 // compact2 runs with a fixed number of workgroups, each owning a short list of matches.
-constexpr uint32_t kMatchBlocksPerRegion = 64;
-constexpr uint32_t kMatchBlocks = kMatchBlocksPerRegion * kCandRegions;      // 1024
+constexpr uint32_t kMatchBlocks = 1024;
 constexpr uint32_t kMatchSlotsPerBlock = 64;
 constexpr uint32_t kMatchSlots = kMatchBlocks * kMatchSlotsPerBlock;         // 65536
 
 // Counters shared by all scopes of one pac_build_mask call.
 struct Globals {
-    unsigned long long cand_total;       // (estimated) undecided elements over all scopes
     uint32_t retry;                      // a sampled bracket missed the k-th element: redo with full counts
     uint32_t match_overflow;             // a workgroup of compact2 ran out of match slots
-    uint32_t overflow;                   // candidate list unusable this call: scopes are resolved in place
     uint32_t scan_ticket;                // next tile of the prefix scan
     uint32_t scan_stalled;               // set if a scan workgroup gave up waiting (never expected)
-    uint32_t pad[2];
-    uint32_t region_fill[kCandRegions * kFillStride];  // entries in region r at [r * kFillStride]
+    uint32_t pad[4];
 };
 
 struct MaskScratch {
@@ -86,14 +84,14 @@ struct MaskScratch {
     SegState* state;               // [max_segments]
     uint32_t* hist0;               // [max_segments * kDigit0Bins], all zero between calls
     uint32_t* hist1;               // [max_segments * kDigit1Bins], all zero between calls
-    uint32_t* kept_above;          // [max_segments * kCandRegions * kFillStride] elements with key >= hi,
-                                   // one padded counter per scope and candidate region
+    uint32_t* kept_above;          // [max_segments] elements with key >= hi (counted for sampled scopes)
     Globals* glob;
-    unsigned long long* cand;      // [cand_cap] composites of undecided elements, kCandRegions regions
-    unsigned long long* match;     // [kMatchSlots] candidates whose digit 1 is their scope's bin1 as well,
-                                   // kMatchSlotsPerBlock slots per workgroup of compact2
+    unsigned long long* rec;       // [tiles * kRecSlots] tile records
+    uint32_t* tile_scope;          // [tiles] scope of each tile's first element (for the current table)
+    unsigned long long* match;     // [kMatchSlots] undecided elements whose digit 1 is their scope's bin1 as
+                                   // well, kMatchSlotsPerBlock slots per workgroup of compact2
     uint32_t* match_count;         // [kMatchBlocks] slots used by each workgroup
-    uint32_t cand_cap;             // multiple of kCandRegions
+    unsigned long long cand_cap;   // undecided elements the records may list in total (a test hook lowers it)
     unsigned long long* tile_state; // per scan tile: status and running count of the look-back scan
 };
 
@@ -101,10 +99,11 @@ struct MaskScratch {
 // first launch error.
 // `sampled_elems`: elements the first histogram pass visits (sum over scopes of length / stride).
 // `max_tiny` / `max_small`: length of the longest small scope of at most kTinyScope elements / of any
-// length in the table (0 = none).
+// length in the table (0 = none).  `table_changed`: the scope table on the device is not the one of
+// the previous call.
 constexpr uint32_t kTinyScope = 4096;
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
-                             uint64_t sampled_elems, uint32_t max_tiny, uint32_t max_small,
+                             uint64_t sampled_elems, uint32_t max_tiny, uint32_t max_small, bool table_changed,
                              unsigned long long* d_mask, uint32_t* d_prefix, int num_cu, hipStream_t stream);
 // Raises the small-scope kernel's LDS limit; once per device, before the first launch.
 hipError_t prepare_mask_kernels();

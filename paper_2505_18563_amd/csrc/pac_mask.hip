@@ -7,21 +7,26 @@
 //   select0  per scope: bracket [lo, hi) of whole digit-0 bins that holds the k-th key - exactly
 //            one bin when every element was counted, the bins inside a confidence band around the
 //            estimated rank when the scope was sampled
-//   emit     one pass over the weights: mask bit = key >= hi, assembled into mask words in
-//            registers; elements with lo <= key < hi are undecided: their composites go to the
-//            candidate list and are counted by digit 1; kept elements are counted per scope
+//   emit     one pass over the weights, one workgroup per 4096-element tile: mask bit = key >= hi,
+//            a compare's lane mask being the mask word; elements with lo <= key < hi are
+//            undecided: their composites go to the tile's record, with the tile's count of kept
+//            elements.  No atomics
+//   count1   from the records: digit-1 histogram of the undecided elements and kept counts per scope
 //   select1  per scope: checks that the bracket did hold the k-th key (always true for exact
 //            counts), then the digit-1 bin b1 of the k-th undecided element and its rank inside
-//   (retry)  if a sampled bracket missed, hist0/select0/emit/select1 run again with full counts;
-//            otherwise those four launches return at once
-//   compact2 candidates whose digit 1 is their scope's b1 -> match lists (a few hundred per scope)
+//   (retry)  if a sampled bracket missed, hist0/select0/emit/count1/select1 run again with full
+//            counts; otherwise those five launches return at once
+//   small    scopes of at most 32768 elements take no part in the above: one workgroup each selects
+//            from LDS and writes the scope's mask bits
+//   compact2 undecided elements whose digit 1 is their scope's b1 -> match lists (a few hundred per scope)
 //   final    one workgroup per scope gathers its matches into LDS and resolves the remaining
 //            bits there -> C*
-//   fixup    candidates with composite >= C* get their mask bit set (atomic OR)
+//   fixup    undecided elements with composite >= C* get their mask bit set (atomic OR)
 //   scan     exclusive prefix sum of the mask-word popcounts (single pass, decoupled look-back)
 //
-// When the undecided elements of a call do not fit the candidate list (very many equal magnitudes)
-// the lists are not used: `final` and `fixup` then walk the weights instead.  Same result, slower.
+// A tile that holds more undecided elements than its record takes (very many equal magnitudes) is
+// not listed: count1, compact2 and fixup read that tile's weights instead.  A scope with more than
+// 4096 matches is resolved by `final` from its weights.  Same results, slower.
 #include <cstdlib>
 
 #include "pac_internal.h"
@@ -110,13 +115,6 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* w
     total = tot;
     __syncthreads();
     return off + inc - v;
-}
-
-// Tiles of a streaming pass are dealt to the persistent workgroups in runs of `run_len`: at any
-// time the running workgroups cover one contiguous window of the tensor.
-constexpr uint32_t kRunLen = 4;
-__device__ __forceinline__ uint32_t tile_of(uint32_t j) {
-    return ((j / kRunLen) * gridDim.x + blockIdx.x) * kRunLen + j % kRunLen;
 }
 
 // ------------------------------------------------------------------------------------- hist0
@@ -283,7 +281,7 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
                                                                    uint32_t pass) {
     constexpr int THREADS = kDigit0Bins / 16;
     __shared__ uint32_t wave_sums[THREADS / 64];
-    __shared__ uint32_t sh_hi, sh_lo, sh_above_hi, sh_in_range;
+    __shared__ uint32_t sh_hi, sh_lo, sh_above_hi;
     if (pass != 0 && !glob->retry) return;
     const uint32_t s = blockIdx.x;
     const uint32_t k = seg[s].k;
@@ -303,8 +301,7 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
     }
 
     // this scope's kept counters start from zero
-    for (uint32_t j = threadIdx.x; j < kCandRegions * kFillStride; j += THREADS)
-        kept_above[(size_t)s * kCandRegions * kFillStride + j] = 0;
+    if (threadIdx.x == 0) kept_above[s] = 0;
 
     // thread t owns bins [16t, 16t+16); read and clear them
     uint32_t loc[16];
@@ -348,7 +345,7 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
         lo_rank = ks - kBandSigmas * sd - 2.0;
         hi_rank = ks + kBandSigmas * sd + 2.0;
     }
-    if (threadIdx.x == 0) { sh_hi = kDigit0Bins - 1; sh_lo = 0; sh_above_hi = 0; sh_in_range = 0; }
+    if (threadIdx.x == 0) { sh_hi = kDigit0Bins - 1; sh_lo = 0; sh_above_hi = 0; }
     __syncthreads();
     {
         // b_hi = smallest bin with (#counted above it) <= lo_rank; b_lo = largest bin with
@@ -369,15 +366,12 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
     const uint32_t b_hi = sh_hi;
     const uint32_t b_lo = min(sh_lo, b_hi);
     {
-        uint32_t cgt = above, in_range = 0;
+        uint32_t cgt = above;
 #pragma unroll
         for (int j = 15; j >= 0; --j) {
-            const uint32_t bin = threadIdx.x * 16 + j;
-            if (bin == b_hi) sh_above_hi = cgt;
-            if (bin >= b_lo && bin <= b_hi) in_range += loc[j];
+            if (threadIdx.x * 16 + j == b_hi) sh_above_hi = cgt;
             cgt += loc[j];
         }
-        if (in_range) atomicAdd(&sh_in_range, in_range);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -390,10 +384,6 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
         st->krem0 = exact ? k - sh_above_hi : 0u;
         st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
         st->heavy = 0;
-        // undecided elements this scope will list (scaled up, with a margin, when sampled)
-        u64 est = sh_in_range;
-        if (!exact) est = (u64)((double)est * ((double)n_s / (double)counted) * 1.25) + 1024;
-        atomicAdd(&glob->cand_total, est);
     }
 }
 
@@ -416,9 +406,7 @@ __global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(const SegDesc
             if (st->exact) {
                 rank = st->krem0;
             } else {
-                uint32_t kept = 0;
-                for (uint32_t r = 0; r < kCandRegions; ++r)
-                    kept += kept_above[((size_t)s * kCandRegions + r) * kFillStride];
+                const uint32_t kept = kept_above[s];
                 const uint32_t k = seg[s].k;
                 rank = k > kept ? k - kept : 0u;   // 0: more than k elements above the bracket
             }
@@ -445,319 +433,407 @@ __global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(const SegDesc
 // The pass over the weights that writes the mask.  With [lo, hi) the scope's bracket:
 // key >= hi -> kept;   lo <= key < hi -> undecided (candidate).
 //
-// Persistent workgroups of 4 waves walk 4096-element tiles, one 1024-element quarter per wave,
-// with streaming 16-byte loads.  A lane owns 4 consecutive elements, i.e. one nibble of a mask
-// word; the 8 lanes that share a 32-bit half of a mask word OR their shifted nibbles together with
-// three DPP steps and one lane stores the half word.
-// Undecided elements are rare for continuous weight distributions.  Their digit-1 counts go to a
-// workgroup LDS histogram (flushed when the workgroup leaves the scope); their composites are
-// staged in workgroup LDS and appended to one region of the candidate list with a single global
-// atomic per flush.  The all-zero composite cannot occur (flat indices are below 2^32 - 1): it
-// marks an empty staging slot.
-// Tiles that are ragged (tensor end), unaligned or cross a scope boundary take a plain path.
+// One workgroup of 4 waves per 4096-element tile, one 1024-element quarter per wave.  A lane loads
+// one element per step (16 dword loads at a stride of 64 elements, all issued before the first is
+// used), so the lane mask of the compare `key >= hi` IS the mask word of those 64 elements: no
+// cross-lane assembly.  Lane u keeps word u; 16 lanes store the wave's 128 bytes of mask.
+// The workgroup ends with stores and takes part in no atomics: a workgroup's wave slots stay taken
+// until its last memory operation is acknowledged, and a returning atomic is the slowest of them.
+//
+// Undecided elements are rare for continuous weight distributions (~0.5 %).  Their composites go,
+// through a small per-wave LDS stage, into the tile's record: 128 u64 slots per tile, slot 0 the
+// header (kept-element count << 32 | listed entries), then the entries.  A tile that holds more
+// undecided elements than its record takes (very many equal magnitudes) is marked kRecWalk: the
+// kernels that consume the records then walk that tile's 4096 weights instead - the overflow is
+// local, every other tile keeps its list.
 constexpr int kEmitBlock = 256;
 constexpr int kEmitWaves = kEmitBlock / 64;
-constexpr uint32_t kEmitLoads = 4;                                  // 16-byte loads per lane per tile
-constexpr uint32_t kEmitWaveTile = 64 * 4 * kEmitLoads;             // 1024 elements = 16 mask words
+constexpr uint32_t kEmitLoads = 16;                                 // dword loads per lane per tile
+constexpr uint32_t kEmitWaveTile = 64 * kEmitLoads;                 // 1024 elements = 16 mask words
 constexpr uint32_t kEmitTile = kEmitWaves * kEmitWaveTile;          // 4096 elements
-constexpr uint32_t kStageCap = 1024;                                // staged composites per workgroup
-constexpr uint32_t kEmitRunLen = kRunLen;                           // tiles per run; staging is checked per run
+constexpr uint32_t kWaveStage = 64;                                 // staged composites per wave
+static_assert(kEmitTile == kEmitTileElems, "records are per emit tile");
 
 struct EmitShared {
-    u64 stage[kStageCap];
-    uint32_t hist1[kDigit1Bins];
-    uint32_t wave_sums[kEmitWaves];
-    uint32_t stage_count;     // slots handed out (may exceed kStageCap: the excess went to global memory)
-    uint32_t flush_base;
-    uint32_t kept;            // elements above the bracket seen by this workgroup in the current scope
+    u64 stage[kEmitWaves][kWaveStage];
+    uint32_t wcount[kEmitWaves];     // staged by each wave, kRecWalk if its stage overflowed
+    uint32_t wkept[kEmitWaves];
 };
 
-__device__ __forceinline__ uint32_t or_over_8_lanes(uint32_t x) {
-    // After the three steps every lane of an aligned group of 8 holds the OR of the group.
-    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
-    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
-    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, true);   // row_half_mirror
-    return x;
+// Scope of element i for a lane whose elements come in ascending order: moves (sc, sc_end) forward.
+// Returns true when the scope changed.  Requires i < n (the last scope ends at n).
+__device__ __forceinline__ bool advance_scope(const SegDesc* __restrict__ seg, uint32_t i, uint32_t& sc,
+                                              uint32_t& sc_end) {
+    bool moved = false;
+    while (i >= sc_end) {
+        ++sc;
+        sc_end = seg[sc].end;
+        moved = true;
+    }
+    return moved;
 }
 
-// Reserves `count` slots in candidate region `r`; returns the first slot, or kNoSlot when the
-// region is full (the call then resolves its scopes in place).
-constexpr uint32_t kNoSlot = 0xFFFFFFFFu;
-__device__ __forceinline__ uint32_t reserve_region(Globals* glob, uint32_t r, uint32_t count, uint32_t region_cap) {
-    const uint32_t base = atomicAdd(&glob->region_fill[r * kFillStride], count);
-    if (base > region_cap || count > region_cap - base) {
-        glob->overflow = 1;
-        return kNoSlot;
-    }
-    return base;
-}
-
-// Moves the staged composites to the workgroup's candidate region.  Called by all threads.
-__device__ __forceinline__ void flush_stage(EmitShared& sh, Globals* glob, u64* __restrict__ cand, uint32_t r,
-                                            uint32_t region_cap) {
-    __syncthreads();
-    if (sh.stage_count != 0) {   // same value for every thread: nothing writes it between the barriers
-        constexpr uint32_t kPer = kStageCap / kEmitBlock;
-        u64 e[kPer];
-        uint32_t have = 0;
-#pragma unroll
-        for (uint32_t j = 0; j < kPer; ++j) {
-            e[j] = sh.stage[threadIdx.x * kPer + j];
-            have += e[j] != 0 ? 1u : 0u;
-        }
-        uint32_t total;
-        uint32_t pos = block_exclusive_scan<kEmitBlock>(have, sh.wave_sums, total);
-        if (threadIdx.x == 0) sh.flush_base = total ? reserve_region(glob, r, total, region_cap) : kNoSlot;
-        __syncthreads();
-        const uint32_t base = sh.flush_base;
-#pragma unroll
-        for (uint32_t j = 0; j < kPer; ++j) {
-            if (e[j] != 0) {
-                if (base != kNoSlot) cand[(size_t)r * region_cap + base + pos] = e[j];
-                ++pos;
-                sh.stage[threadIdx.x * kPer + j] = 0;
-            }
-        }
-        if (threadIdx.x == 0) sh.stage_count = 0;
-    }
-    __syncthreads();
-}
-
-// Adds the workgroup's digit-1 counts and its count of kept elements to the scope's totals.
-__device__ __forceinline__ void flush_scope(EmitShared& sh, uint32_t kept_in_lane, uint32_t* __restrict__ global_hist1,
-                                            uint32_t* __restrict__ kept_counter) {
-    const uint32_t wave_kept = wave_sum(kept_in_lane);
-    if (lane_id() == 0 && wave_kept) atomicAdd(&sh.kept, wave_kept);
-    __syncthreads();
-    for (uint32_t b = threadIdx.x; b < kDigit1Bins; b += kEmitBlock) {
-        const uint32_t v = sh.hist1[b];
-        if (v) {
-            atomicAdd(&global_hist1[b], v);
-            sh.hist1[b] = 0;
-        }
-    }
-    if (threadIdx.x == 0) {
-        if (sh.kept) atomicAdd(kept_counter, sh.kept);
-        sh.kept = 0;
-    }
-    __syncthreads();
-}
-
-template <bool VEC>
-#ifndef PAC_EXP_EMIT_WAVES
-#define PAC_EXP_EMIT_WAVES 1
-#endif
-__global__ __launch_bounds__(kEmitBlock, PAC_EXP_EMIT_WAVES) void emit_kernel(const float* __restrict__ w, uint32_t n,
+__global__ __launch_bounds__(kEmitBlock, 8) void emit_kernel(const float* __restrict__ w, uint32_t n,
                                                           const SegDesc* __restrict__ seg, uint32_t nseg,
-                                                          const SegState* __restrict__ state, Globals* glob,
-                                                          uint32_t* __restrict__ hist1,
-                                                          uint32_t* __restrict__ kept_above, u64* __restrict__ cand,
-                                                          uint32_t cand_cap, u64* __restrict__ mask, uint32_t pass) {
+                                                          const SegState* __restrict__ state, const Globals* glob,
+                                                          const uint32_t* __restrict__ tile_scope,
+                                                          uint32_t* __restrict__ kept_above, u64* __restrict__ rec,
+                                                          uint32_t rec_cap, u64* __restrict__ mask, uint32_t pass) {
     __shared__ EmitShared sh;
     if (pass != 0 && !glob->retry) return;             // the retry pass has nothing to do
-    for (uint32_t j = threadIdx.x; j < kDigit1Bins; j += kEmitBlock) sh.hist1[j] = 0;
-    for (uint32_t j = threadIdx.x; j < kStageCap; j += kEmitBlock) sh.stage[j] = 0;
-    if (threadIdx.x == 0) { sh.stage_count = 0; sh.flush_base = 0; sh.kept = 0; }
-    __syncthreads();
-
     const uint32_t lane = lane_id();
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t region = blockIdx.x % kCandRegions;
-    const uint32_t region_cap = cand_cap / kCandRegions;
-    // The number of undecided elements is known (or estimated) from the histogram pass; if they cannot
-    // fit, none is listed.
-    const bool listing = glob->cand_total <= (u64)cand_cap;
-    if (!listing && blockIdx.x == 0 && threadIdx.x == 0) glob->overflow = 1;
-
     const uint32_t num_tiles = (uint32_t)(((u64)n + kEmitTile - 1) / kEmitTile);
-    const uint32_t kNone = 0xFFFFFFFFu;
-    uint32_t cur = kNone;                        // scope whose digit-1 counts sit in LDS
-    uint32_t cur_begin = 0, cur_end = 0, s_lo = 0, s_hi = 0, s_sh1 = 0;
-    bool s_list = false;                         // undecided elements of scope `cur` go to the candidate list
-    uint32_t kept_in_lane = 0;                   // elements of scope `cur` above its bracket, this lane
-    auto kept_slot = [&](uint32_t scope) {
-        return kept_above + ((size_t)scope * kCandRegions + region) * kFillStride;
-    };
+    const uint32_t words = (uint32_t)(((u64)n + 63) >> 6);
 
-    for (uint32_t j = 0;; ++j) {
-        const uint32_t t = tile_of(j);
-        if (t >= num_tiles) break;
-        const uint32_t a = t * kEmitTile;                               // < n
-        const uint32_t b = (uint32_t)min((u64)a + kEmitTile, (u64)n);
-        const bool whole = VEC && b - a == kEmitTile;
-        const u64 wave_first = (u64)a + wave * kEmitWaveTile;
-        u32x4 v[kEmitLoads];
+    for (uint32_t t = blockIdx.x; t < num_tiles;) {                  // one trip when the grid covers the tiles
+        const u64 a = (u64)t * kEmitTile;                            // < n
+        const bool whole = a + kEmitTile <= n;
+        const u64 wave_first = a + wave * kEmitWaveTile;
+        uint32_t v[kEmitLoads];
         if (whole) {
-            const u32x4* p = reinterpret_cast<const u32x4*>(w + wave_first) + lane;
+            const uint32_t* p = reinterpret_cast<const uint32_t*>(w) + wave_first + lane;
 #pragma unroll
             for (uint32_t u = 0; u < kEmitLoads; ++u) v[u] = __builtin_nontemporal_load(p + u * 64);
-        }
-
-        if (listing && j % kEmitRunLen == 0 && j != 0) {
-            // A run adds at most a few hundred composites below the listing limit; make room for it.
-            __syncthreads();
-            const uint32_t staged = sh.stage_count;
-            __syncthreads();
-            if (staged >= kStageCap / 2) flush_stage(sh, glob, cand, region, region_cap);
-        }
-
-        uint32_t s0 = cur;
-        if (cur == kNone || a < cur_begin || a >= cur_end) s0 = find_seg(seg, nseg, a);
-        const uint32_t s0_end = s0 == cur ? cur_end : seg[s0].end;
-        const bool single = s0_end >= b;                                // whole tile inside one scope
-        if (single && s0 != cur) {                                      // same decision in every wave
-            if (cur != kNone) flush_scope(sh, kept_in_lane, hist1 + (size_t)cur * kDigit1Bins, kept_slot(cur));
-            kept_in_lane = 0;
-            cur = s0;
-            cur_begin = seg[s0].begin;
-            cur_end = s0_end;
-            s_lo = state[s0].lo;
-            s_hi = state[s0].hi;
-            s_sh1 = state[s0].sh1;
-            s_list = listing;
-        }
-
-        if (single && whole) {
-            uint32_t und_bits = 0;   // bit 4u+e: element e of load u is undecided
-            const uint32_t width = s_hi - s_lo;
+        } else {
 #pragma unroll
             for (uint32_t u = 0; u < kEmitLoads; ++u) {
-                const uint32_t k0 = key_of_bits(v[u].x), k1 = key_of_bits(v[u].y);
-                const uint32_t k2 = key_of_bits(v[u].z), k3 = key_of_bits(v[u].w);
-                const uint32_t nib = (k0 >= s_hi ? 1u : 0u) | (k1 >= s_hi ? 2u : 0u) | (k2 >= s_hi ? 4u : 0u) |
-                                     (k3 >= s_hi ? 8u : 0u);
-                kept_in_lane += (uint32_t)__popc(nib);
-                const uint32_t half = or_over_8_lanes(nib << ((lane & 7u) * 4u));
-                const u64 first = wave_first + u * 256u;                // first element of this wave step
-#ifdef PAC_EXP_EMIT_NT
-                if ((lane & 7u) == 0)
-                    __builtin_nontemporal_store(half, reinterpret_cast<uint32_t*>(mask) + (first >> 5) + (lane >> 3));
-#else
-                if ((lane & 7u) == 0)
-                    reinterpret_cast<uint32_t*>(mask)[(first >> 5) + (lane >> 3)] = half;
-#endif
-                const uint32_t und = (k0 - s_lo < width ? 1u : 0u) | (k1 - s_lo < width ? 2u : 0u) |
-                                     (k2 - s_lo < width ? 4u : 0u) | (k3 - s_lo < width ? 8u : 0u);
-                und_bits |= und << (4u * u);
+                const u64 i = wave_first + u * 64 + lane;
+                v[u] = i < n ? __float_as_uint(w[i]) : 0u;
             }
-            // Undecided elements, one per lane and round (a lane rarely holds more than one).
-            while (true) {
-                const bool has = und_bits != 0;
-                const u64 cm = __ballot(has);
-                if (cm == 0) break;
-                const uint32_t pick = has ? (uint32_t)__ffs((int)und_bits) - 1u : 0u;
-                und_bits &= und_bits - 1u;
-                const u32x4 q = (pick & 8u) ? ((pick & 4u) ? v[3] : v[2]) : ((pick & 4u) ? v[1] : v[0]);
-                const uint32_t raw = (pick & 2u) ? ((pick & 1u) ? q.w : q.z) : ((pick & 1u) ? q.y : q.x);
-                const uint32_t key = key_of_bits(raw);
-                if (has) atomicAdd(&sh.hist1[(key - s_lo) >> s_sh1], 1u);
-                if (s_list) {
-                    const uint32_t count = (uint32_t)__popcll(cm);
-                    const uint32_t i = (uint32_t)wave_first + (pick >> 2) * 256u + lane * 4u + (pick & 3u);
-                    uint32_t base = 0;
-                    if (lane == 0) base = atomicAdd(&sh.stage_count, count);
-                    base = __builtin_amdgcn_readfirstlane(base);
-                    if (base + count <= kStageCap) {
-                        if (has) sh.stage[base + lanes_below(cm)] = composite_of(key, i);
+        }
+        const uint32_t s0 = nseg > 1 ? tile_scope[t] : 0u;
+        const uint32_t s0_end = seg[s0].end;
+
+        u64 mine = 0;                 // lane u: mask word u of this wave
+        uint32_t staged = 0, kept_n = 0;
+        bool over = false;
+        u64* my = sh.stage[wave];
+        if (whole && (u64)s0_end >= a + kEmitTile) {
+            // the whole tile inside one scope: nothing per element but the two compares
+            const uint32_t lo = state[s0].lo, hi = state[s0].hi, width = hi - lo;
+            const uint32_t i0 = (uint32_t)wave_first + lane;
+#pragma unroll
+            for (uint32_t u = 0; u < kEmitLoads; ++u) {
+                const uint32_t key = key_of_bits(v[u]);
+                const u64 km = __ballot(key >= hi);
+                kept_n += (uint32_t)__popcll(km);
+                if (lane == u) mine = km;
+                const bool und = key - lo < width;
+                const u64 cm = __ballot(und);
+                if (cm != 0) {
+                    const uint32_t c = (uint32_t)__popcll(cm);
+                    if (staged + c <= kWaveStage) {
+                        if (und) my[staged + lanes_below(cm)] = composite_of(key, i0 + u * 64);
                     } else {
-                        // staging area full: straight to the candidate region
-                        uint32_t g = 0;
-                        if (lane == 0) g = reserve_region(glob, region, count, region_cap);
-                        g = __builtin_amdgcn_readfirstlane(g);
-                        if (has && g != kNoSlot)
-                            cand[(size_t)region * region_cap + g + lanes_below(cm)] = composite_of(key, i);
+                        over = true;
                     }
+                    staged += c;
                 }
             }
         } else {
-            // Plain path: every lane handles 4 consecutive elements with its own bounds and scopes.  A
-            // lane's elements come in ascending order, so its scope only moves forward from the scope of
-            // the tile's first element; counters are bumped once per wave and distinct target.
+            // The ragged last tile, or a tile that crosses scope boundaries: every lane follows the
+            // scopes of its own (ascending) elements.  Kept counts of sampled scopes go straight to
+            // their counters (the record's count is only used for tiles inside one scope).
+            const bool single = (u64)s0_end >= min(a + kEmitTile, (u64)n);
             uint32_t sc = s0, sc_end = s0_end;
-            uint32_t lo = state[s0].lo, hi = state[s0].hi, sh1 = state[s0].sh1, exact = state[s0].exact;
-#pragma unroll 1
+            uint32_t lo = state[s0].lo, hi = state[s0].hi, exact = state[s0].exact;
+#pragma unroll
             for (uint32_t u = 0; u < kEmitLoads; ++u) {
-                const u64 first = wave_first + u * 256u;
-                uint32_t nib = 0;
-#pragma unroll 1
-                for (uint32_t e = 0; e < 4; ++e) {
-                    const u64 i64 = first + lane * 4u + e;
-                    const uint32_t i = (uint32_t)i64;
-                    bool kept = false, undecided = false, append = false;
-                    uint32_t key = 0, d1 = 0;
-                    if (i64 < n) {
-                        while (i >= sc_end) {           // ends: the last scope ends at n > i
-                            ++sc;
-                            sc_end = seg[sc].end;
-                            if (i < sc_end) { lo = state[sc].lo; hi = state[sc].hi; sh1 = state[sc].sh1; exact = state[sc].exact; }
-                        }
-                        key = key_of_bits(__float_as_uint(w[i]));
-                        kept = key >= hi;
-                        undecided = !kept && key >= lo;
-                        if (undecided) d1 = (key - lo) >> sh1;
-                        append = undecided && listing;
-                        if (kept) nib |= 1u << e;
-                        kept = kept && !exact;          // only sampled scopes need the count
-                    }
-                    wave_aggregated_inc(kept_above, (sc * kCandRegions + region) * kFillStride, kept);
-                    wave_aggregated_inc(hist1, sc * kDigit1Bins + d1, undecided);
-                    const u64 am = __ballot(append);
-                    if (am != 0) {
-                        uint32_t g = 0;
-                        if (lane == 0) g = reserve_region(glob, region, (uint32_t)__popcll(am), region_cap);
-                        g = __builtin_amdgcn_readfirstlane(g);
-                        if (append && g != kNoSlot)
-                            cand[(size_t)region * region_cap + g + lanes_below(am)] = composite_of(key, i);
-                    }
+                const u64 i = wave_first + u * 64 + lane;
+                const bool valid = i < n;
+                if (valid && advance_scope(seg, (uint32_t)i, sc, sc_end)) {
+                    lo = state[sc].lo; hi = state[sc].hi; exact = state[sc].exact;
                 }
-                const uint32_t half = or_over_8_lanes(nib << ((lane & 7u) * 4u));
-                const u64 half_idx = (first >> 5) + (lane >> 3);
-                if ((lane & 7u) == 0 && half_idx < 2 * (((u64)n + 63) >> 6))
-                    reinterpret_cast<uint32_t*>(mask)[half_idx] = half;
+                const uint32_t key = key_of_bits(v[u]);
+                const bool kept = valid && key >= hi;
+                const u64 km = __ballot(kept);
+                kept_n += (uint32_t)__popcll(km);
+                if (lane == u) mine = km;
+                if (!single) wave_aggregated_inc(kept_above, sc, kept && !exact);
+                const bool und = valid && key - lo < hi - lo;
+                const u64 cm = __ballot(und);
+                if (cm != 0) {
+                    const uint32_t c = (uint32_t)__popcll(cm);
+                    if (staged + c <= kWaveStage) {
+                        if (und) my[staged + lanes_below(cm)] = composite_of(key, (uint32_t)i);
+                    } else {
+                        over = true;
+                    }
+                    staged += c;
+                }
             }
         }
+        if (lane < kEmitLoads) {
+            const u64 wi = (wave_first >> 6) + lane;
+            if (wi < words) __builtin_nontemporal_store(mine, mask + wi);
+        }
+
+        // the tile's record: header, then the waves' entries back to back
+        if (lane == 0) {
+            sh.wcount[wave] = over ? kRecWalk : staged;
+            sh.wkept[wave] = kept_n;
+        }
+        __syncthreads();
+        uint32_t off = 0, total = 0, kept_total = 0;
+        bool walk = false;
+#pragma unroll
+        for (int j = 0; j < kEmitWaves; ++j) {
+            const uint32_t c = sh.wcount[j];
+            if (c == kRecWalk) {
+                walk = true;
+            } else {
+                if ((uint32_t)j < wave) off += c;
+                total += c;
+            }
+            kept_total += sh.wkept[j];
+        }
+        if (total > rec_cap) walk = true;
+        u64* r = rec + (size_t)t * kRecSlots;
+        if (threadIdx.x == 0) r[0] = ((u64)kept_total << 32) | (walk ? kRecWalk : total);
+        if (!walk) {
+            for (uint32_t j = lane; j < staged; j += 64) r[1 + off + j] = my[j];
+        }
+        t += gridDim.x;
+        if (t >= num_tiles) break;
+        __syncthreads();   // the stage and the counts are reused by the next tile
     }
-    if (listing) flush_stage(sh, glob, cand, region, region_cap);
-    if (cur != kNone) flush_scope(sh, kept_in_lane, hist1 + (size_t)cur * kDigit1Bins, kept_slot(cur));
+}
+
+// First scope of every emit tile, so that a workgroup finds its scope with one load.
+__global__ void tile_scope_kernel(const SegDesc* __restrict__ seg, uint32_t nseg, uint32_t num_tiles,
+                                  uint32_t* __restrict__ tile_scope) {
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < num_tiles) tile_scope[t] = find_seg(seg, nseg, t * kEmitTile);
+}
+
+// ---------------------------------------------------------------------- walking the tile records
+// count1, compact2 and fixup all visit "every undecided element": the entries of the tiles'
+// records, or, for a tile marked kRecWalk, the tile's weights.  A wave takes 64 tiles at a time, one
+// header per lane, then runs over the entries of all 64 records as one flat sequence (an entry
+// finds its tile by a search over the running counts), so that the loads of a step are independent
+// of each other.  `header(t, hdr, s0, single)` is called once per tile by its lane,
+// `visit(composite, scope)` by the lanes that hold an undecided element, under divergence.
+struct WalkShared {
+    uint32_t excl[64];     // entries in the records of the lanes below
+    uint32_t meta[64];     // tile's first scope | bit 31: the tile lies inside that scope
+};
+
+__device__ __forceinline__ void wave_lds_sync() {
+    // Orders this wave's LDS writes before its later LDS reads of other lanes' data.
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+    const uint32_t lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(v, d, 64);
+        if (lane >= (uint32_t)d) v += t;
+    }
+    return v;
+}
+
+template <typename Header, typename Visit>
+__device__ __forceinline__ void visit_tiles(const float* __restrict__ w, uint32_t n,
+                                            const SegDesc* __restrict__ seg, uint32_t nseg,
+                                            const SegState* __restrict__ state,
+                                            const uint32_t* __restrict__ tile_scope, const u64* __restrict__ rec,
+                                            uint32_t t0, uint32_t t_end, WalkShared& ws, Header header,
+                                            Visit visit) {
+    const uint32_t lane = lane_id();
+    const uint32_t t = t0 + lane;
+    const bool valid = t < t_end;
+    const u64 hdr = valid ? rec[(size_t)t * kRecSlots] : 0ull;
+    const uint32_t s0 = valid && nseg > 1 ? tile_scope[t] : 0u;
+    const bool single = valid && (u64)seg[s0].end >= min((u64)(t + 1) * kEmitTile, (u64)n);
+    if (valid) header(t, hdr, s0, single);
+    const uint32_t cnt = (uint32_t)hdr;
+    const bool walk = valid && cnt == kRecWalk;
+    const uint32_t c = valid && !walk ? cnt : 0u;
+    const uint32_t incl = wave_inclusive_scan(c);
+    const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    wave_lds_sync();                       // the previous step's readers are done
+    ws.excl[lane] = incl - c;
+    ws.meta[lane] = s0 | (single ? 0x80000000u : 0u);
+    wave_lds_sync();
+    constexpr uint32_t kAhead = 4;         // entry loads in flight per lane
+    for (uint32_t e0 = 0; e0 < total; e0 += 64 * kAhead) {
+        u64 cmp[kAhead];
+        uint32_t m[kAhead];
+#pragma unroll
+        for (uint32_t q = 0; q < kAhead; ++q) {
+            const uint32_t e = e0 + q * 64 + lane;
+            cmp[q] = 0;
+            m[q] = 0;
+            if (e < total) {
+                uint32_t j = 0;            // the last lane whose running count does not exceed e owns entry e
+#pragma unroll
+                for (uint32_t step = 32; step >= 1; step >>= 1)
+                    if (ws.excl[j + step] <= e) j += step;   // j + step <= 63
+                cmp[q] = rec[(size_t)(t0 + j) * kRecSlots + 1 + (e - ws.excl[j])];
+                m[q] = ws.meta[j];
+            }
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < kAhead; ++q) {
+            if (e0 + q * 64 + lane < total)
+                visit(cmp[q], (m[q] & 0x80000000u) ? (m[q] & 0x7FFFFFFFu) : find_seg(seg, nseg, index_of(cmp[q])));
+        }
+    }
+    // tiles whose undecided elements are not listed: the wave reads their weights
+    u64 todo = __ballot(walk);
+    while (todo != 0) {
+        const uint32_t j = (uint32_t)__ffsll((long long)todo) - 1u;
+        todo &= todo - 1;
+        const uint32_t tw = t0 + j;
+        const u64 a = (u64)tw * kEmitTile;
+        const u64 b = min(a + kEmitTile, (u64)n);
+        uint32_t sc = nseg > 1 ? tile_scope[tw] : 0u;
+        uint32_t sc_end = seg[sc].end;
+        uint32_t lo = state[sc].lo, hi = state[sc].hi;
+        for (u64 i = a + lane; i < b; i += 64) {
+            if (advance_scope(seg, (uint32_t)i, sc, sc_end)) { lo = state[sc].lo; hi = state[sc].hi; }
+            const uint32_t key = key_of_bits(__float_as_uint(w[i]));
+            if (key - lo < hi - lo) visit(composite_of(key, (uint32_t)i), sc);
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------- count1
+// Digit-1 histogram of the undecided elements and, for sampled scopes, the number of elements above
+// the bracket, per scope.  Few large workgroups, each over a contiguous range of tiles, so that
+// the counts of a range meet in one LDS histogram before they go to the global one.  A workgroup
+// works in rounds of up to 1024 tiles that start in the same scope; what a round meets of another
+// scope (in a tile that crosses a boundary) is counted in global memory.
+constexpr int kCountBlock = 1024;
+constexpr uint32_t kCountBlocks = 256;
+
+__global__ __launch_bounds__(kCountBlock) void count1_kernel(const float* __restrict__ w, uint32_t n,
+                                                             const SegDesc* __restrict__ seg, uint32_t nseg,
+                                                             const SegState* __restrict__ state, const Globals* glob,
+                                                             const uint32_t* __restrict__ tile_scope,
+                                                             const u64* __restrict__ rec,
+                                                             uint32_t* __restrict__ hist1,
+                                                             uint32_t* __restrict__ kept_above, uint32_t pass) {
+    constexpr uint32_t kWaves = kCountBlock / 64;
+    __shared__ uint32_t lds[kDigit1Bins];
+    __shared__ WalkShared ws[kWaves];
+    __shared__ uint32_t sh_kept;
+    if (pass != 0 && !glob->retry) return;
+    for (uint32_t b = threadIdx.x; b < kDigit1Bins; b += kCountBlock) lds[b] = 0;
+    if (threadIdx.x == 0) sh_kept = 0;
+    __syncthreads();
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t num_tiles = (uint32_t)(((u64)n + kEmitTile - 1) / kEmitTile);
+    const uint32_t per_block = (num_tiles + gridDim.x - 1) / gridDim.x;
+    const uint32_t t_begin = min(num_tiles, blockIdx.x * per_block);
+    const uint32_t t_end = min(num_tiles, t_begin + per_block);
+    const uint32_t kNone = 0xFFFFFFFFu;
+    uint32_t cur = kNone;    // scope whose counts sit in LDS (same in every thread)
+
+    auto flush = [&]() {
+        __syncthreads();
+        for (uint32_t b = threadIdx.x; b < kDigit1Bins; b += kCountBlock) {
+            const uint32_t v = lds[b];
+            if (v) {
+                atomicAdd(&hist1[(size_t)cur * kDigit1Bins + b], v);
+                lds[b] = 0;
+            }
+        }
+        if (threadIdx.x == 0) {
+            if (sh_kept) atomicAdd(&kept_above[cur], sh_kept);
+            sh_kept = 0;
+        }
+        __syncthreads();
+    };
+
+    uint32_t t = t_begin;
+    while (t < t_end) {                                         // same trips in every thread
+        const uint32_t s_round = nseg > 1 ? tile_scope[t] : 0u;
+        uint32_t r_end = min(t_end, t + kWaves * 64);
+        if (nseg > 1 && tile_scope[r_end - 1] != s_round) {
+            // the round stops before the first tile that starts in another scope (tile_scope ascends)
+            uint32_t lo_t = t, hi_t = r_end - 1;                // tile_scope[lo_t] == s_round < tile_scope[hi_t]
+            while (hi_t - lo_t > 1) {
+                const uint32_t mid = (lo_t + hi_t) >> 1;
+                if (tile_scope[mid] == s_round) lo_t = mid; else hi_t = mid;
+            }
+            r_end = hi_t;
+        }
+        if (s_round != cur) {
+            if (cur != kNone) flush();
+            cur = s_round;
+        }
+        const uint32_t t0 = t + wave * 64;
+        if (t0 < r_end) {
+            visit_tiles(w, n, seg, nseg, state, tile_scope, rec, t0, r_end, ws[wave],
+                [&](uint32_t, u64 hdr, uint32_t s0, bool single) {
+                    // kept elements of a tile inside one scope (emit counted the others itself)
+                    const uint32_t kept = (uint32_t)(hdr >> 32);
+                    if (single && kept != 0 && !state[s0].exact) {
+                        if (s0 == cur) atomicAdd(&sh_kept, kept);
+                        else atomicAdd(&kept_above[s0], kept);
+                    }
+                },
+                [&](u64 c, uint32_t s) {
+                    const uint32_t d1 = ((uint32_t)(c >> 32) - state[s].lo) >> state[s].sh1;
+                    if (s == cur) atomicAdd(&lds[d1], 1u);
+                    else atomicAdd(&hist1[(size_t)s * kDigit1Bins + d1], 1u);
+                });
+        }
+        t = r_end;
+    }
+    if (cur != kNone) flush();
 }
 
 // ----------------------------------------------------------------------------------- compact2
-// Walks the candidate regions; a composite whose digit 1 equals its scope's bin is a match.  There
-// are only a few hundred matches per scope, and an append counter shared by all workgroups would
-// cost one serialised global atomic per match; instead every workgroup collects its matches in LDS
-// and writes them to slots of its own, with their number, for `final` to pick up.
+// An undecided element whose digit 1 equals its scope's bin is a match.  There are only a few
+// hundred matches per scope, and an append counter shared by all workgroups would cost one
+// serialised global atomic per match; instead every workgroup collects the matches of its tiles in
+// LDS and writes them to slots of its own, with their number, for `final` to pick up.
 constexpr int kListBlock = 256;
+constexpr uint32_t kListWaves = kMatchBlocks * (kListBlock / 64);   // waves of a compact2 / fixup launch
 
-__global__ __launch_bounds__(kListBlock) void compact2_kernel(const SegDesc* __restrict__ seg, uint32_t nseg,
+// Tiles [begin, end) of wave `gw` out of kListWaves: contiguous, equal shares.
+__device__ __forceinline__ void wave_tile_range(uint32_t num_tiles, uint32_t gw, uint32_t& begin, uint32_t& end) {
+    const uint32_t per_wave = (num_tiles + kListWaves - 1) / kListWaves;
+    begin = min(num_tiles, gw * per_wave);
+    end = min(num_tiles, begin + per_wave);
+}
+
+__global__ __launch_bounds__(kListBlock) void compact2_kernel(const float* __restrict__ w, uint32_t n,
+                                                              const SegDesc* __restrict__ seg, uint32_t nseg,
                                                               const SegState* __restrict__ state, Globals* glob,
-                                                              const u64* __restrict__ cand, uint32_t cand_cap,
-                                                              u64* __restrict__ match,
+                                                              const uint32_t* __restrict__ tile_scope,
+                                                              const u64* __restrict__ rec, u64* __restrict__ match,
                                                               uint32_t* __restrict__ match_count) {
     __shared__ u64 found[kMatchSlotsPerBlock];
+    __shared__ WalkShared ws[kListBlock / 64];
     __shared__ uint32_t nfound;
-    const uint32_t block_id = blockIdx.y * gridDim.x + blockIdx.x;   // < kMatchBlocks by the launch shape
     if (threadIdx.x == 0) nfound = 0;
     __syncthreads();
-    if (!glob->overflow) {
-        const uint32_t r = blockIdx.y;
-        const uint32_t region_cap = cand_cap / kCandRegions;
-        const uint32_t fill = min(glob->region_fill[r * kFillStride], region_cap);
-        const u64* src = cand + (size_t)r * region_cap;
-        for (u64 j = (u64)blockIdx.x * kListBlock + threadIdx.x; j < fill; j += (u64)gridDim.x * kListBlock) {
-            const u64 c = src[j];
-            const uint32_t s = nseg > 1 ? find_seg(seg, nseg, index_of(c)) : 0u;
-            if (!state[s].heavy && (((uint32_t)(c >> 32) - state[s].lo) >> state[s].sh1) == state[s].bin1) {
-                const uint32_t pos = atomicAdd(&nfound, 1u);
-                if (pos < kMatchSlotsPerBlock) found[pos] = c;
-            }
-        }
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t num_tiles = (uint32_t)(((u64)n + kEmitTile - 1) / kEmitTile);
+    uint32_t t_begin, t_end;
+    wave_tile_range(num_tiles, blockIdx.x * (kListBlock / 64) + wave, t_begin, t_end);
+    for (uint32_t t0 = t_begin; t0 < t_end; t0 += 64) {
+        visit_tiles(w, n, seg, nseg, state, tile_scope, rec, t0, t_end, ws[wave],
+            [](uint32_t, u64, uint32_t, bool) {},
+            [&](u64 c, uint32_t s) {
+                if (!state[s].heavy && (((uint32_t)(c >> 32) - state[s].lo) >> state[s].sh1) == state[s].bin1) {
+                    const uint32_t pos = atomicAdd(&nfound, 1u);
+                    if (pos < kMatchSlotsPerBlock) found[pos] = c;
+                }
+            });
     }
     __syncthreads();
     const uint32_t total = nfound;
     if (total > kMatchSlotsPerBlock && threadIdx.x == 0) glob->match_overflow = 1;   // `final` uses the weights
     const uint32_t kept = min(total, kMatchSlotsPerBlock);
-    if (threadIdx.x < kept) match[(size_t)block_id * kMatchSlotsPerBlock + threadIdx.x] = found[threadIdx.x];
-    if (threadIdx.x == 0) match_count[block_id] = kept;
+    if (threadIdx.x < kept) match[(size_t)blockIdx.x * kMatchSlotsPerBlock + threadIdx.x] = found[threadIdx.x];
+    if (threadIdx.x == 0) match_count[blockIdx.x] = kept;
 }
 
 // -------------------------------------------------------------------------------------- final
@@ -829,7 +905,7 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
     const uint32_t begin = seg[s].begin, end = seg[s].end;
     if (threadIdx.x == 0) { found[0] = 0; found[1] = 0; gathered = 0; }
     __syncthreads();
-    const bool from_list = !glob->overflow && !glob->match_overflow && !st->heavy;
+    const bool from_list = !glob->match_overflow && !st->heavy;
     if (from_list) {
         // Matches of this scope: thread t looks through the slots of compact2's workgroup t.
         static_assert(kFinalBlock == (int)kMatchBlocks, "one thread per compact2 workgroup");
@@ -969,45 +1045,27 @@ __global__ __launch_bounds__(kSmallBlock) void small_scope_kernel(const float* _
 // Undecided elements at or above their scope's C* are kept: set their mask bits.
 __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restrict__ w, uint32_t n,
                                                            const SegDesc* __restrict__ seg, uint32_t nseg,
-                                                           const SegState* __restrict__ state, const Globals* glob,
-                                                           const u64* __restrict__ cand, uint32_t cand_cap,
-                                                           u64* __restrict__ mask, u64* __restrict__ tile_state,
-                                                           uint32_t scan_tiles) {
+                                                           const SegState* __restrict__ state,
+                                                           const uint32_t* __restrict__ tile_scope,
+                                                           const u64* __restrict__ rec, u64* __restrict__ mask,
+                                                           u64* __restrict__ tile_state, uint32_t scan_tiles) {
+    __shared__ WalkShared ws[kListBlock / 64];
     // The scan that follows starts from cleared tile states.
-    for (u64 j = ((u64)blockIdx.y * gridDim.x + blockIdx.x) * kListBlock + threadIdx.x; j < scan_tiles;
-         j += (u64)gridDim.x * gridDim.y * kListBlock)
+    for (u64 j = (u64)blockIdx.x * kListBlock + threadIdx.x; j < scan_tiles; j += (u64)gridDim.x * kListBlock)
         tile_state[j] = 0;
-    if (!glob->overflow) {
-        const uint32_t r = blockIdx.y;
-        const uint32_t region_cap = cand_cap / kCandRegions;
-        const uint32_t fill = min(glob->region_fill[r * kFillStride], region_cap);
-        const u64* src = cand + (size_t)r * region_cap;
-        for (u64 j = (u64)blockIdx.x * kListBlock + threadIdx.x; j < fill; j += (u64)gridDim.x * kListBlock) {
-            const u64 c = src[j];
-            const uint32_t i = index_of(c);
-            const uint32_t s = nseg > 1 ? find_seg(seg, nseg, i) : 0u;
-            if (c >= state[s].cstar) atomicOr(&mask[i >> 6], 1ull << (i & 63u));
-        }
-    } else {
-        // Lists not in use: walk the weights.
-        const u64 tid = ((u64)blockIdx.y * gridDim.x + blockIdx.x) * kListBlock + threadIdx.x;
-        const u64 nthreads = (u64)gridDim.x * gridDim.y * kListBlock;
-        const uint32_t kNone = 0xFFFFFFFFu;
-        uint32_t s = kNone, s_begin = 0, s_end = 0, lo = 0, hi = 0;
-        u64 cstar = 0;
-        for (u64 i = tid; i < n; i += nthreads) {
-            if (s == kNone || i < s_begin || i >= s_end) {
-                s = find_seg(seg, nseg, (uint32_t)i);
-                s_begin = seg[s].begin;
-                s_end = seg[s].end;
-                lo = state[s].lo;
-                hi = state[s].hi;
-                cstar = state[s].cstar;
-            }
-            const uint32_t key = key_of_bits(__float_as_uint(w[i]));
-            if (key >= lo && key < hi && composite_of(key, (uint32_t)i) >= cstar)
-                atomicOr(&mask[i >> 6], 1ull << (i & 63u));
-        }
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t num_tiles = (uint32_t)(((u64)n + kEmitTile - 1) / kEmitTile);
+    uint32_t t_begin, t_end;
+    wave_tile_range(num_tiles, blockIdx.x * (kListBlock / 64) + wave, t_begin, t_end);
+    for (uint32_t t0 = t_begin; t0 < t_end; t0 += 64) {
+        visit_tiles(w, n, seg, nseg, state, tile_scope, rec, t0, t_end, ws[wave],
+            [](uint32_t, u64, uint32_t, bool) {},
+            [&](u64 c, uint32_t s) {
+                if (c >= state[s].cstar) {
+                    const uint32_t i = index_of(c);
+                    atomicOr(&mask[i >> 6], 1ull << (i & 63u));
+                }
+            });
     }
 }
 
@@ -1033,17 +1091,6 @@ __device__ __forceinline__ u64 tile_load(const u64* p) {
 }
 __device__ __forceinline__ void tile_store(u64* p, u64 v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Inclusive prefix sum over the 64 lanes of a wave.
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
-    const uint32_t lane = lane_id();
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t t = __shfl_up(v, d, 64);
-        if (lane >= (uint32_t)d) v += t;
-    }
-    return v;
 }
 
 __global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __restrict__ mask, uint32_t words,
@@ -1171,18 +1218,23 @@ hipError_t prepare_mask_kernels() {
 }
 
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
-                             uint64_t sampled_elems, uint32_t max_tiny, uint32_t max_small,
+                             uint64_t sampled_elems, uint32_t max_tiny, uint32_t max_small, bool table_changed,
                              unsigned long long* d_mask, uint32_t* d_prefix, int num_cu, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     const uint32_t words = div_up_u64(n, 64);
     const bool aligned = (reinterpret_cast<uintptr_t>(d_weights) & 15u) == 0;
+    const uint32_t hist_tiles = div_up_u64(n, kHistTile), emit_tiles = div_up_u64(n, kEmitTile);
+
+    if (table_changed && nseg > 1)
+        hipLaunchKernelGGL(tile_scope_kernel, dim3(div_up_u64(emit_tiles, 256)), dim3(256), 0, stream, s.seg, nseg,
+                           emit_tiles, s.tile_scope);
 
     static const uint32_t hist_want = resident_blocks(hist0_kernel<true>, kHistBlock, num_cu, 2);
-    static const uint32_t emit_want = resident_blocks(emit_kernel<true>, kEmitBlock, num_cu, 4);
-    const uint32_t hist_tiles = div_up_u64(n, kHistTile), emit_tiles = div_up_u64(n, kEmitTile);
     const uint32_t hist_grid = hist_tiles < hist_want ? hist_tiles : hist_want;
-    const uint32_t emit_grid = emit_tiles < emit_want ? emit_tiles : emit_want;
-    // Pass 0 works from (possibly sampled) histograms; pass 1 repeats the four kernels with full
+    // a record takes what the candidate capacity allows per tile (all of its slots unless a test lowered it)
+    const uint32_t per_tile = (uint32_t)(s.cand_cap / emit_tiles);
+    const uint32_t rec_cap = per_tile < kRecSlots - 1 ? per_tile : kRecSlots - 1;
+    // Pass 0 works from (possibly sampled) histograms; pass 1 repeats the five kernels with full
     // counts if a sampled bracket missed, and returns at once otherwise.
     for (uint32_t pass = 0; pass < 2; ++pass) {
         // The sampled pass visits few tiles: no more workgroups than tiles.
@@ -1199,14 +1251,14 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
                                s.seg, nseg, s.hist0, s.glob, pass);
         hipLaunchKernelGGL(select0_kernel, dim3(nseg), dim3(kDigit0Bins / 16), 0, stream, s.seg, s.state, s.hist0,
                            s.kept_above, s.glob, pass);
-        if (aligned)
-            hipLaunchKernelGGL((emit_kernel<true>), dim3(emit_grid), dim3(kEmitBlock), 0, stream, d_weights, n,
-                               s.seg, nseg, s.state, s.glob, s.hist1, s.kept_above, s.cand, s.cand_cap, d_mask,
-                               pass);
-        else
-            hipLaunchKernelGGL((emit_kernel<false>), dim3(emit_grid), dim3(kEmitBlock), 0, stream, d_weights, n,
-                               s.seg, nseg, s.state, s.glob, s.hist1, s.kept_above, s.cand, s.cand_cap, d_mask,
-                               pass);
+        // One workgroup per tile; the retry pass, which almost never runs, strides over the tiles
+        // with a small grid so that its launch costs little.
+        const uint32_t emit_grid = pass == 0 || emit_tiles < 2048 ? emit_tiles : 2048u;
+        hipLaunchKernelGGL(emit_kernel, dim3(emit_grid), dim3(kEmitBlock), 0, stream, d_weights, n, s.seg, nseg,
+                           s.state, s.glob, s.tile_scope, s.kept_above, s.rec, rec_cap, d_mask, pass);
+        const uint32_t count_grid = emit_tiles < kCountBlocks ? emit_tiles : kCountBlocks;
+        hipLaunchKernelGGL(count1_kernel, dim3(count_grid), dim3(kCountBlock), 0, stream, d_weights, n, s.seg, nseg,
+                           s.state, s.glob, s.tile_scope, s.rec, s.hist1, s.kept_above, pass);
         hipLaunchKernelGGL(select1_kernel, dim3(nseg), dim3(kDigit1Bins / 16), 0, stream, s.seg, s.state, s.hist1,
                            s.kept_above, s.glob, pass);
     }
@@ -1219,17 +1271,13 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
         hipLaunchKernelGGL((small_scope_kernel<1024, kSmallScope>), dim3(nseg), dim3(1024),
                            (size_t)max_small * sizeof(uint32_t), stream, d_weights, s.seg, d_mask, kTinyScope + 1u);
 
-    const uint32_t list_blocks = 256;   // per candidate region
-    static_assert(kListBlock == 256, "compact2 runs 4 waves per workgroup");
-    hipLaunchKernelGGL(compact2_kernel, dim3(kMatchBlocksPerRegion, kCandRegions), dim3(kListBlock), 0, stream,
-                       s.seg, nseg, s.state, s.glob, s.cand, s.cand_cap, s.match, s.match_count);
+    hipLaunchKernelGGL(compact2_kernel, dim3(kMatchBlocks), dim3(kListBlock), 0, stream, d_weights, n, s.seg, nseg,
+                       s.state, s.glob, s.tile_scope, s.rec, s.match, s.match_count);
     hipLaunchKernelGGL(final_kernel, dim3(nseg), dim3(kFinalBlock), 0, stream, d_weights, s.seg, s.state, s.glob,
                        s.match, s.match_count);
-    hipLaunchKernelGGL(fixup_kernel, dim3(list_blocks, kCandRegions), dim3(kListBlock), 0, stream, d_weights, n,
-                       s.seg, nseg, s.state, s.glob, s.cand, s.cand_cap, d_mask, s.tile_state,
-                       div_up_u64(words, kScanTile));
-
     const uint32_t scan_tiles = div_up_u64(words, kScanTile);
+    hipLaunchKernelGGL(fixup_kernel, dim3(kMatchBlocks), dim3(kListBlock), 0, stream, d_weights, n, s.seg, nseg,
+                       s.state, s.tile_scope, s.rec, d_mask, s.tile_state, scan_tiles);
     hipLaunchKernelGGL(scan_lookback_kernel, dim3(scan_tiles), dim3(kScanBlock), 0, stream, d_mask, words,
                        s.tile_state, s.glob, d_prefix, static_cast<u64*>(nullptr));
     return hipGetLastError();

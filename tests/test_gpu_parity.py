@@ -141,17 +141,19 @@ def test_build_mask_many_small_segments(ctx):
     check_mask(ctx, w, off, sp, "400 small scopes")
 
 
-def test_build_mask_in_place_selection_when_candidates_do_not_fit(pac):
-    """A tiny candidate list forces the scopes with many equal magnitudes onto the in-place path."""
-    rng = np.random.default_rng(23)
+@pytest.mark.parametrize("capacity", [0, 1000, 4000])
+def test_build_mask_tiles_whose_undecided_elements_are_not_listed(pac, capacity):
+    """A lowered listing capacity leaves most or all 4096-element tiles without a list of their undecided
+    elements: the later passes then read those tiles' weights."""
+    rng = np.random.default_rng(23 + capacity)
     c = pac.PacContext(max_elems=1 << 21, max_segments=8, device=0)
     try:
-        pac.pac_debug_set_candidate_capacity(c.handle, 1000)
+        pac.pac_debug_set_candidate_capacity(c.handle, capacity)
         n = 300000
         for kind in ("equal", "ties", "zeros_half", "gauss"):
             w = weights_of(kind, n, rng)
-            check_mask(c, w, [0, n], 0.7, f"small-capacity {kind}")
-            check_mask(c, w, [0, 1000, 150000, 150001, n], [0.5, 0.9, 0.0, 0.3], f"small-capacity segmented {kind}")
+            check_mask(c, w, [0, n], 0.7, f"capacity {capacity} {kind}")
+            check_mask(c, w, [0, 1000, 150000, 150001, n], [0.5, 0.9, 0.0, 0.3], f"capacity {capacity} segmented {kind}")
     finally:
         c.close()
 
