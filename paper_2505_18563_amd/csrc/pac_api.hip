@@ -265,12 +265,14 @@ pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n, cons
     // Keep counts: host arithmetic, so the total is known without waiting for the device.
     std::vector<pac::SegDesc> table(nseg);
     uint64_t total = 0, sampled = 0;
+    bool any_sampled = false;
     uint32_t max_small = 0, max_tiny = 0;   // longest small scope of the table, and longest of the tiny class
     for (uint32_t s = 0; s < nseg; ++s) {
         const uint64_t b = h_seg_offsets[s], e = h_seg_offsets[s + 1];
         const uint64_t k = pac_keep_count(e - b, h_sparsity[s]);
         table[s] = pac::SegDesc{(uint32_t)b, (uint32_t)e, (uint32_t)k, sample_stride(e - b)};
         total += k;
+        if (table[s].stride > 1) any_sampled = true;
         if (table[s].stride != 0) sampled += (e - b) / table[s].stride;
         else {
             if (e - b > max_small) max_small = (uint32_t)(e - b);
@@ -308,7 +310,7 @@ pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n, cons
         ctx->table_valid = true;
     }
 
-    hipError_t r = pac::launch_build_mask(ctx->scratch, d_weights, (uint32_t)n, nseg, sampled, max_tiny, max_small,
+    hipError_t r = pac::launch_build_mask(ctx->scratch, d_weights, (uint32_t)n, nseg, sampled, any_sampled, max_tiny, max_small,
                                           !same, reinterpret_cast<unsigned long long*>(d_mask), d_prefix, ctx->num_cu, stream);
     if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_build_mask: launch: %s", hipGetErrorString(r));
     return PAC_OK;

@@ -98,13 +98,14 @@ struct MaskScratch {
 // Launchers (defined in pac_mask.hip / pac_pack.hip).  All enqueue on `stream` and return the
 // first launch error.
 // `sampled_elems`: elements the first histogram pass visits (sum over scopes of length / stride).
-// `max_tiny` / `max_small`: length of the longest small scope of at most kTinyScope elements / of any
+// `any_sampled`: some scope has a stride above 1.  `max_tiny` / `max_small`: length of the longest small scope of at most kTinyScope elements / of any
 // length in the table (0 = none).  `table_changed`: the scope table on the device is not the one of
 // the previous call.
 constexpr uint32_t kTinyScope = 4096;
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
-                             uint64_t sampled_elems, uint32_t max_tiny, uint32_t max_small, bool table_changed,
-                             unsigned long long* d_mask, uint32_t* d_prefix, int num_cu, hipStream_t stream);
+                             uint64_t sampled_elems, bool any_sampled, uint32_t max_tiny, uint32_t max_small,
+                             bool table_changed, unsigned long long* d_mask, uint32_t* d_prefix, int num_cu,
+                             hipStream_t stream);
 // Raises the small-scope kernel's LDS limit; once per device, before the first launch.
 hipError_t prepare_mask_kernels();
 

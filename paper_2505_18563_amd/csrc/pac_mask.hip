@@ -1218,8 +1218,9 @@ hipError_t prepare_mask_kernels() {
 }
 
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
-                             uint64_t sampled_elems, uint32_t max_tiny, uint32_t max_small, bool table_changed,
-                             unsigned long long* d_mask, uint32_t* d_prefix, int num_cu, hipStream_t stream) {
+                             uint64_t sampled_elems, bool any_sampled, uint32_t max_tiny, uint32_t max_small,
+                             bool table_changed, unsigned long long* d_mask, uint32_t* d_prefix, int num_cu,
+                             hipStream_t stream) {
     if (n == 0) return hipSuccess;
     const uint32_t words = div_up_u64(n, 64);
     const bool aligned = (reinterpret_cast<uintptr_t>(d_weights) & 15u) == 0;
@@ -1236,7 +1237,8 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
     const uint32_t rec_cap = per_tile < kRecSlots - 1 ? per_tile : kRecSlots - 1;
     // Pass 0 works from (possibly sampled) histograms; pass 1 repeats the five kernels with full
     // counts if a sampled bracket missed, and returns at once otherwise.
-    for (uint32_t pass = 0; pass < 2; ++pass) {
+    // (A table with no sampled scope cannot miss: the second round is not even launched.)
+    for (uint32_t pass = 0; pass < (any_sampled ? 2u : 1u); ++pass) {
         // The sampled pass visits few tiles: no more workgroups than tiles.
         uint32_t grid = hist_grid;
         if (pass == 0) {
