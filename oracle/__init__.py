@@ -53,6 +53,14 @@ def _load():
         lib.orc_mask_from_nonzero.argtypes = [vp, i32, u64, vp, vp]
         lib.orc_mask_diff.restype = u64
         lib.orc_mask_diff.argtypes = [vp, vp, u64]
+        lib.orc_philox4x32_10.restype = None
+        lib.orc_philox4x32_10.argtypes = [vp, vp, vp]
+        lib.orc_absmax.restype = ctypes.c_float
+        lib.orc_absmax.argtypes = [vp, i32, u64, vp]
+        lib.orc_ternarize.restype = None
+        lib.orc_ternarize.argtypes = [vp, i32, u64, ctypes.c_float, u64, u64, vp]
+        lib.orc_ternary_reduce.restype = None
+        lib.orc_ternary_reduce.argtypes = [vp, u32, u64, ctypes.c_float, i32, vp]
         lib.orc_decompress_update.restype = u64
         lib.orc_decompress_update.argtypes = [vp, i32, u64, vp, ctypes.c_float, vp, u64]
         _lib = lib
@@ -184,3 +192,36 @@ def decompress_update(compact: np.ndarray, mask: np.ndarray, weights: np.ndarray
     if used != c.size:
         raise ValueError(f"mask holds {used} set bits, compact buffer has {c.size}")
     return w
+
+
+# ---- ternary payload (Sec. III-D) -----------------------------------------------------------
+
+def philox4x32_10(counter, key) -> np.ndarray:
+    c = np.ascontiguousarray(counter, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.empty(4, dtype=np.uint32)
+    _load().orc_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def absmax(values: np.ndarray, dtype: int = F32, start=None) -> float:
+    v = np.ascontiguousarray(values, dtype=_elem_dtype(dtype)).reshape(-1)
+    st = None if start is None else np.array([start], dtype=np.float32)
+    return float(_load().orc_absmax(_ptr(v), dtype, v.size, None if st is None else _ptr(st)))
+
+
+def ternarize(values: np.ndarray, scale: float, seed: int, stream: int, dtype: int = F32) -> np.ndarray:
+    """Packed 2-bit codes (0 = 0, 1 = +1, 2 = -1), four elements per byte, element j at bits 2*(j%4)."""
+    v = np.ascontiguousarray(values, dtype=_elem_dtype(dtype)).reshape(-1)
+    out = np.empty((v.size + 3) // 4, dtype=np.uint8)
+    _load().orc_ternarize(_ptr(v), dtype, v.size, ctypes.c_float(scale), int(seed), int(stream), _ptr(out))
+    return out
+
+
+def ternary_reduce(packed, count: int, scale: float, out_dtype: int = F32) -> np.ndarray:
+    arrs = [np.ascontiguousarray(p, dtype=np.uint8).reshape(-1) for p in packed]
+    assert all(a.size >= (count + 3) // 4 for a in arrs)
+    ptrs = (ctypes.c_void_p * len(arrs))(*[_ptr(a) for a in arrs])
+    out = np.empty(count, dtype=_elem_dtype(out_dtype))
+    _load().orc_ternary_reduce(ctypes.addressof(ptrs), len(arrs), count, ctypes.c_float(scale), out_dtype, _ptr(out))
+    return out

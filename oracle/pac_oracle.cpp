@@ -280,4 +280,91 @@ uint64_t orc_decompress_update(const void* compact, int dtype, uint64_t nnz, con
     return next;
 }
 
+// ---- ternary payload (Sec. III-D "Pruning with Gradient Quantization") ---------------------
+// ternarize(.) of Sec. III-D is the TernGrad quantiser the section names: with a scale s >= max|g|,
+// every element becomes s * sign(g) * b with b ~ Bernoulli(|g| / s), so that E[s * t] = g (Eq. 3 is
+// that expectation).  The paper fixes neither the random source nor the layout; here:
+//  * random bits: the Philox4x32-10 counter-based generator (Salmon et al., SC'11), key = the two
+//    halves of `seed`, counter = (block, block >> 32, stream, stream >> 32) with block = j / 4; the
+//    four output words serve elements 4*block .. 4*block+3.  A worker passes its own `stream`.
+//  * u = (word >> 8) * 2^-24, a uniform in [0,1) that is exact in single precision;
+//    p = |g| / s as one IEEE single division; the element is kept iff u < p.
+//  * code 0 = 0, 1 = +1, 2 = -1; element j sits in bits 2*(j%4).. of byte j/4; unused bits zero.
+//  * a scale that is zero, negative, infinite or NaN, and NaN elements, give code 0.
+//  * the scale is shared by the workers (TernGrad's scaler sharing), so that the ternaries can be
+//    summed as integers by an all-reduce: sum = s * (float)(t_0 + ... + t_{W-1}).
+
+static inline void philox_round(uint32_t c[4], uint32_t k0, uint32_t k1) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c[0];
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c[2];
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c[1] ^ k0;
+    const uint32_t n1 = (uint32_t)p1;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c[3] ^ k1;
+    const uint32_t n3 = (uint32_t)p0;
+    c[0] = n0; c[1] = n1; c[2] = n2; c[3] = n3;
+}
+
+// Philox4x32 with 10 rounds; the key is bumped by the Weyl constants between rounds.
+void orc_philox4x32_10(const uint32_t counter[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c[4] = {counter[0], counter[1], counter[2], counter[3]};
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        philox_round(c, k0, k1);
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    for (int i = 0; i < 4; ++i) out[i] = c[i];
+}
+
+// max |x| over the buffer, NaN elements ignored; 0 for an empty buffer.  If `start` is given the
+// result is max(*start, max|x|): calls over the W workers' buffers build the shared scale.
+float orc_absmax(const void* values, int dtype, uint64_t count, const float* start) {
+    float m = start ? *start : 0.0f;
+    for (uint64_t j = 0; j < count; ++j) {
+        const float x = dtype == ORC_F32 ? static_cast<const float*>(values)[j]
+                                         : bf16_to_float(static_cast<const uint16_t*>(values)[j]);
+        const float a = std::fabs(x);
+        if (a > m) m = a;          // false for NaN
+    }
+    return m;
+}
+
+void orc_ternarize(const void* values, int dtype, uint64_t count, float scale, uint64_t seed, uint64_t stream,
+                   uint8_t* packed) {
+    const uint64_t bytes = (count + 3) / 4;
+    for (uint64_t b = 0; b < bytes; ++b) packed[b] = 0;
+    const bool usable = scale > 0.0f && !std::isinf(scale);     // false for NaN too
+    if (!usable) return;
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (uint64_t block = 0; block * 4 < count; ++block) {
+        const uint32_t counter[4] = {(uint32_t)block, (uint32_t)(block >> 32), (uint32_t)stream, (uint32_t)(stream >> 32)};
+        uint32_t r[4];
+        orc_philox4x32_10(counter, key, r);
+        for (uint64_t e = 0; e < 4 && block * 4 + e < count; ++e) {
+            const uint64_t j = block * 4 + e;
+            const float x = dtype == ORC_F32 ? static_cast<const float*>(values)[j]
+                                             : bf16_to_float(static_cast<const uint16_t*>(values)[j]);
+            const float u = (float)(r[e] >> 8) * 5.9604644775390625e-08f;     // 2^-24, exact
+            const float p = std::fabs(x) / scale;
+            if (u < p) packed[j >> 2] |= (uint8_t)((std::signbit(x) ? 2u : 1u) << (2 * (j & 3)));
+        }
+    }
+}
+
+// out[j] = scale * (float)(t_0[j] + ... + t_{W-1}[j]): an exact integer sum, one multiply, and for a
+// bf16 output one rounding to nearest even.
+void orc_ternary_reduce(const uint8_t* const* packed, uint32_t W, uint64_t count, float scale, int out_dtype,
+                        void* out) {
+    for (uint64_t j = 0; j < count; ++j) {
+        int32_t sum = 0;
+        for (uint32_t w = 0; w < W; ++w) {
+            const uint32_t code = (packed[w][j >> 2] >> (2 * (j & 3))) & 3u;
+            sum += code == 1 ? 1 : code == 2 ? -1 : 0;
+        }
+        const float v = scale * (float)sum;
+        if (out_dtype == ORC_F32) static_cast<float*>(out)[j] = v;
+        else static_cast<uint16_t*>(out)[j] = float_to_bf16_rne(v);
+    }
+}
+
 }  // extern "C"
