@@ -213,11 +213,22 @@ def main() -> int:
             "decompress_update": (lambda: pac.pac_decompress_update(h, red, mask, prefix, 1e-3, w_copy, nnz0),
                                   e * nnz0 + meta + 8 * n),
         }
+        # ternary payload (Sec. III-D) on the compact buffers of this workload
+        t_scale = torch.zeros(1, dtype=torch.float32, device=dev)
+        t_packed = [torch.empty((nnz0 + 3) // 4, dtype=torch.uint8, device=dev) for _ in range(W)]
+        pac.pac_absmax(h, compact[0], t_scale, count=nnz0)
+        for w in range(W):
+            pac.pac_ternarize(h, compact[w], t_scale, 1, w, t_packed[w], count=nnz0)
+        calls["absmax_per_worker"] = (lambda: pac.pac_absmax(h, compact[0], t_scale, accumulate=True, count=nnz0), e * nnz0)
+        calls["ternarize_per_worker"] = (lambda: pac.pac_ternarize(h, compact[0], t_scale, 1, 0, t_packed[0], count=nnz0),
+                                         e * nnz0 + nnz0 // 4)
+        calls["ternary_reduce_local"] = (lambda: pac.pac_ternary_reduce_local(h, t_packed, t_scale, red, nnz0),
+                                         W * (nnz0 // 4) + e * nnz0)
         for name, (fn, nbytes) in calls.items():
             ms = time_call(fn)
             around[name] = {"ms": round(ms, 4), "algorithmic_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
         tracker.close()
-        del w_copy, mask2, prefix2
+        del w_copy, mask2, prefix2, t_packed
 
     k_avg = sum(k_by_phase[(args.warmup + t) % len(schedule)] for t in range(args.steps)) / args.steps
     alg = algorithmic_bytes(n, int(k_avg), W, e)

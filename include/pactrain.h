@@ -164,6 +164,37 @@ pac_status pac_decompress_update(pac_ctx* ctx, const void* d_reduced, pac_dtype 
                                  const uint64_t* d_mask, const uint32_t* d_prefix, float alpha,
                                  float* d_weights, uint64_t n, void* hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Ternary payload (paper Sec. III-D "Pruning with Gradient Quantization": ternarize(g) quantises
+ * the gradient at random into {-1, 0, +1} times a scale, unbiased in expectation, Eq. 3).  The
+ * quantiser is the TernGrad one the section names: with a scale s >= max|g| shared by the workers,
+ * element -> s * sign(g) * b, b ~ Bernoulli(|g| / s).  It is applied to the compact buffers; the
+ * workers' ternaries are then summed as integers and scaled once.
+ *   random bits  Philox4x32-10 (Salmon et al., SC'11), key = (seed, seed >> 32), counter =
+ *                (j / 4, (j / 4) >> 32, stream_id, stream_id >> 32); output word j % 4 serves
+ *                element j.  A worker passes its own stream_id; a step its own seed.
+ *   decision     u = (word >> 8) * 2^-24; kept iff u < |g| / s (one IEEE single division)
+ *   codes        0 = 0, 1 = +1, 2 = -1; element j in bits 2*(j%4).. of byte j/4; unused bits zero
+ *   degenerate   a scale that is zero, negative, infinite or NaN, and NaN elements, give code 0
+ * Packed buffers hold ceil(count / 4) bytes and must be 4-byte aligned.
+ * ------------------------------------------------------------------------------------------ */
+
+/* *d_scale (DEVICE float) = max |x| over the buffer, NaN elements ignored (0 for an empty buffer).
+ * With accumulate != 0 the result is max(old *d_scale, max|x|): one call per worker builds the
+ * shared scale (the old value must be a non-negative number). */
+pac_status pac_absmax(pac_ctx* ctx, const void* d_values, pac_dtype dtype, uint64_t count, int accumulate,
+                      float* d_scale_inout, void* hip_stream);
+
+pac_status pac_ternarize(pac_ctx* ctx, const void* d_values, pac_dtype dtype, uint64_t count,
+                         const float* d_scale, uint64_t seed, uint64_t stream_id, uint8_t* d_packed_out,
+                         void* hip_stream);
+
+/* d_out[j] = *d_scale * (float)(t_0[j] + ... + t_{W-1}[j]): exact integer sum, one single-precision
+ * multiply, one round-to-nearest-even for a PAC_BF16 output.  h_d_packed is a HOST array of W device
+ * pointers, read before the call returns.  1 <= W <= PAC_MAX_WORKERS. */
+pac_status pac_ternary_reduce_local(pac_ctx* ctx, const uint8_t* const* h_d_packed, uint32_t W, uint64_t count,
+                                    const float* d_scale, pac_dtype out_dtype, void* d_out, void* hip_stream);
+
 /* Test hook: lower the number of undecided elements pac_build_mask lists between its selection passes
  * (elements in total; each 4096-element tile gets its share, at most 127).  Tiles whose undecided
  * elements do not fit are re-read from the weights by the later passes; results are identical.

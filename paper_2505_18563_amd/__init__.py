@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     pac_build_mask, pac_compress, pac_create, pac_debug_set_candidate_capacity, pac_decompress,
     pac_destroy, pac_keep_count, pac_last_error, pac_mask_words, pac_reduce_local,
     MaskTracker, pac_decompress_update, pac_mask_equal, pac_mask_from_nonzero, pac_tracker_create,
-    pac_tracker_destroy, pac_tracker_update,
+    pac_tracker_destroy, pac_tracker_update, pac_absmax, pac_ternarize, pac_ternary_reduce_local,
 )

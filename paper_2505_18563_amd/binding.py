@@ -72,6 +72,12 @@ def load_library() -> ctypes.CDLL:
     lib.pac_tracker_update.argtypes = [vp, vp, u64, vp, vp]
     lib.pac_tracker_destroy.restype = i32
     lib.pac_tracker_destroy.argtypes = [vp]
+    lib.pac_absmax.restype = i32
+    lib.pac_absmax.argtypes = [vp, vp, i32, u64, ctypes.c_int, vp, vp]
+    lib.pac_ternarize.restype = i32
+    lib.pac_ternarize.argtypes = [vp, vp, i32, u64, vp, u64, u64, vp, vp]
+    lib.pac_ternary_reduce_local.restype = i32
+    lib.pac_ternary_reduce_local.argtypes = [vp, ctypes.POINTER(vp), u32, u64, vp, i32, vp, vp]
     lib.pac_decompress_update.restype = i32
     lib.pac_decompress_update.argtypes = [vp, vp, i32, u64, vp, vp, ctypes.c_float, vp, u64, vp]
     _lib = lib
@@ -263,6 +269,47 @@ def pac_decompress_update(ctx, reduced: torch.Tensor, mask: torch.Tensor, prefix
     st = load_library().pac_decompress_update(ctx, _dev_ptr(reduced), dt, int(nnz), _dev_ptr(mask), _dev_ptr(prefix),
                                               ctypes.c_float(alpha), _dev_ptr(weights), weights.numel(),
                                               _stream_ptr(stream))
+    _check(ctx, st)
+
+
+def pac_absmax(ctx, values: torch.Tensor, scale: torch.Tensor, accumulate: bool = False, count: Optional[int] = None,
+               stream=None) -> None:
+    """scale: device float32 [1]."""
+    dt = _dtype_code(values)
+    if scale.dtype != torch.float32 or scale.numel() < 1:
+        raise TypeError("scale must be a float32 tensor")
+    n = values.numel() if count is None else int(count)
+    st = load_library().pac_absmax(ctx, _dev_ptr(values) if n else 0, dt, n, 1 if accumulate else 0, _dev_ptr(scale),
+                                   _stream_ptr(stream))
+    _check(ctx, st)
+
+
+def pac_ternarize(ctx, values: torch.Tensor, scale: torch.Tensor, seed: int, stream_id: int, packed: torch.Tensor,
+                  count: Optional[int] = None, stream=None) -> None:
+    """packed: device uint8 [ceil(count/4)], 4-byte aligned."""
+    dt = _dtype_code(values)
+    n = values.numel() if count is None else int(count)
+    if packed.dtype != torch.uint8 or packed.numel() < (n + 3) // 4:
+        raise ValueError("packed must be uint8 with ceil(count/4) elements")
+    if scale.dtype != torch.float32:
+        raise TypeError("scale must be float32")
+    st = load_library().pac_ternarize(ctx, _dev_ptr(values), dt, n, _dev_ptr(scale), int(seed) & (2**64 - 1),
+                                      int(stream_id) & (2**64 - 1), _dev_ptr(packed), _stream_ptr(stream))
+    _check(ctx, st)
+
+
+def pac_ternary_reduce_local(ctx, packed: Sequence[torch.Tensor], scale: torch.Tensor, out: torch.Tensor, count: int,
+                             stream=None) -> None:
+    dt = _dtype_code(out)
+    W = len(packed)
+    for p in packed:
+        if p.dtype != torch.uint8 or p.numel() < (count + 3) // 4:
+            raise ValueError("packed buffers must be uint8 with ceil(count/4) elements")
+    if out.numel() < count:
+        raise ValueError("output buffer too short")
+    ptrs = (ctypes.c_void_p * max(W, 1))(*[_dev_ptr(p) for p in packed])
+    st = load_library().pac_ternary_reduce_local(ctx, ptrs, W, int(count), _dev_ptr(scale), dt, _dev_ptr(out),
+                                                 _stream_ptr(stream))
     _check(ctx, st)
 
 

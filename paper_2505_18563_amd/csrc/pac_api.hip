@@ -517,4 +517,67 @@ pac_status pac_decompress_update(pac_ctx* ctx, const void* d_reduced, pac_dtype 
     return PAC_OK;
 }
 
+// ---- ternary payload ---------------------------------------------------------------------------
+
+pac_status pac_absmax(pac_ctx* ctx, const void* d_values, pac_dtype dtype, uint64_t count, int accumulate,
+                      float* d_scale_inout, void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    const char* who = "pac_absmax";
+    if (dtype != PAC_F32 && dtype != PAC_BF16) return fail(ctx, PAC_ERR_ARG, "%s: unknown dtype %d", who, (int)dtype);
+    if (count >= (1ull << 32)) return fail(ctx, PAC_ERR_RANGE, "%s: count must be below 2^32", who);
+    if (!d_scale_inout || (count > 0 && !d_values)) return fail(ctx, PAC_ERR_ARG, "%s: NULL device pointer", who);
+    if (!is_aligned(d_values, elem_size(dtype)) || !is_aligned(d_scale_inout, 4))
+        return fail(ctx, PAC_ERR_ALIGN, "%s: pointer not aligned to its element size", who);
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: hipSetDevice: %s", who, hipGetErrorString(guard.status));
+    hipError_t r = pac::launch_absmax(d_values, (int)dtype, (uint32_t)count, accumulate != 0, d_scale_inout,
+                                      static_cast<hipStream_t>(hip_stream));
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: launch: %s", who, hipGetErrorString(r));
+    return PAC_OK;
+}
+
+pac_status pac_ternarize(pac_ctx* ctx, const void* d_values, pac_dtype dtype, uint64_t count, const float* d_scale,
+                         uint64_t seed, uint64_t stream_id, uint8_t* d_packed_out, void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    const char* who = "pac_ternarize";
+    if (dtype != PAC_F32 && dtype != PAC_BF16) return fail(ctx, PAC_ERR_ARG, "%s: unknown dtype %d", who, (int)dtype);
+    if (count >= (1ull << 32)) return fail(ctx, PAC_ERR_RANGE, "%s: count must be below 2^32", who);
+    if (count == 0) return PAC_OK;
+    if (!d_values || !d_scale || !d_packed_out) return fail(ctx, PAC_ERR_ARG, "%s: NULL device pointer", who);
+    if (!is_aligned(d_values, elem_size(dtype)) || !is_aligned(d_scale, 4) || !is_aligned(d_packed_out, 4))
+        return fail(ctx, PAC_ERR_ALIGN, "%s: misaligned pointer (packed buffers need 4 bytes)", who);
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: hipSetDevice: %s", who, hipGetErrorString(guard.status));
+    hipError_t r = pac::launch_ternarize(d_values, (int)dtype, (uint32_t)count, d_scale, seed, stream_id, d_packed_out,
+                                         static_cast<hipStream_t>(hip_stream));
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: launch: %s", who, hipGetErrorString(r));
+    return PAC_OK;
+}
+
+pac_status pac_ternary_reduce_local(pac_ctx* ctx, const uint8_t* const* h_d_packed, uint32_t W, uint64_t count,
+                                    const float* d_scale, pac_dtype out_dtype, void* d_out, void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    const char* who = "pac_ternary_reduce_local";
+    if (out_dtype != PAC_F32 && out_dtype != PAC_BF16) return fail(ctx, PAC_ERR_ARG, "%s: unknown dtype %d", who, (int)out_dtype);
+    if (W < 1 || W > PAC_MAX_WORKERS) return fail(ctx, PAC_ERR_RANGE, "%s: W=%u not in [1, %u]", who, W, PAC_MAX_WORKERS);
+    if (count >= (1ull << 32)) return fail(ctx, PAC_ERR_RANGE, "%s: count must be below 2^32", who);
+    if (!h_d_packed) return fail(ctx, PAC_ERR_ARG, "%s: pointer table is NULL", who);
+    if (count == 0) return PAC_OK;
+    pac::WorkerPtrs bufs;
+    for (uint32_t w = 0; w < PAC_MAX_WORKERS; ++w) bufs.p[w] = nullptr;
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!h_d_packed[w]) return fail(ctx, PAC_ERR_ARG, "%s: buffer %u is NULL", who, w);
+        if (!is_aligned(h_d_packed[w], 4)) return fail(ctx, PAC_ERR_ALIGN, "%s: buffer %u not 4-byte aligned", who, w);
+        bufs.p[w] = h_d_packed[w];
+    }
+    if (!d_out || !d_scale) return fail(ctx, PAC_ERR_ARG, "%s: NULL device pointer", who);
+    if (!is_aligned(d_out, elem_size(out_dtype)) || !is_aligned(d_scale, 4)) return fail(ctx, PAC_ERR_ALIGN, "%s: misaligned pointer", who);
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: hipSetDevice: %s", who, hipGetErrorString(guard.status));
+    hipError_t r = pac::launch_ternary_reduce(bufs, W, (uint32_t)count, d_scale, (int)out_dtype, d_out,
+                                              static_cast<hipStream_t>(hip_stream));
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: launch: %s", who, hipGetErrorString(r));
+    return PAC_OK;
+}
+
 }  // extern "C"

@@ -148,6 +148,15 @@ struct WorkerPtrs {
     const void* p[64];
 };
 
+// Ternary payload (pac_ternary.hip).  *d_scale is a device float.
+hipError_t launch_absmax(const void* d_values, int dtype, uint32_t count, bool accumulate, float* d_scale,
+                         hipStream_t stream);
+hipError_t launch_ternarize(const void* d_values, int dtype, uint32_t count, const float* d_scale,
+                            unsigned long long seed, unsigned long long stream_id, uint8_t* d_packed,
+                            hipStream_t stream);
+hipError_t launch_ternary_reduce(const WorkerPtrs& bufs, uint32_t W, uint32_t count, const float* d_scale,
+                                 int out_dtype, void* d_out, hipStream_t stream);
+
 hipError_t launch_reduce(const WorkerPtrs& bufs, uint32_t W, int dtype, uint32_t nnz, void* d_out,
                          hipStream_t stream);
 
