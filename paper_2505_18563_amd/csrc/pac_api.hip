@@ -78,13 +78,13 @@ bool is_aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t
 
 uint32_t elem_size(pac_dtype dt) { return dt == PAC_F32 ? 4u : 2u; }
 
-// Stride of the sampled histogram pass over one prune scope: scopes below 8M elements are counted
-// in full; larger ones keep at least about 4M sampled elements, at most one 16384-element tile in 16.
+// Stride of the sampled histogram pass over one prune scope: scopes below 4M elements are counted
+// in full; larger ones keep at least about 2M sampled elements, at most one 16384-element tile in 16.
 // 0 marks a small scope.
 uint32_t sample_stride(uint64_t len) {
     if (len <= pac::kSmallScope) return 0;   // small scope: resolved by one workgroup, outside the histogram passes
     uint32_t stride = 1;
-    while (stride < pac::kMaxSampleStride && len / (2ull * stride) >= (1ull << 22)) stride *= 2;
+    while (stride < pac::kMaxSampleStride && len / (2ull * stride) >= (1ull << 21)) stride *= 2;
     return stride;
 }
 

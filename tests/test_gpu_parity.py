@@ -160,7 +160,7 @@ def test_build_mask_tiles_whose_undecided_elements_are_not_listed(pac, capacity)
 
 @pytest.mark.parametrize("kind", ["gauss", "ties", "zeros_half"])
 def test_build_mask_large_scope_sampled_histogram(ctx, kind):
-    """Scopes above 8M elements get their bracket from a sampled histogram; the mask is exact all the same."""
+    """Scopes above 4M elements get their bracket from a sampled histogram; the mask is exact all the same."""
     rng = np.random.default_rng(51)
     n = 20_000_003
     w = weights_of(kind, n, rng)
