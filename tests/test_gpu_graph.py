@@ -1,0 +1,70 @@
+"""The whole step captured in a HIP graph: the library launches kernels only (no memset, no allocation,
+no host synchronisation once the scope table is on the device), so a step can be recorded once and
+replayed.  Every replay is checked against the eager result, with eager work and synchronisations of the
+program's own between the replays and fresh inputs in the captured buffers."""
+import numpy as np
+import pytest
+import torch
+
+from synth import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("config_id", [1, 2])
+def test_step_replays_from_a_graph(config_id):
+    import paper_2505_18563_amd as pac
+    dev = torch.device("cuda", 0)
+    wl = make_workload(config_id, device=dev)
+    n, W = wl.n, wl.workers
+    sp = wl.sparsity_at(0)
+    nseg = len(wl.scope_offsets) - 1
+    ctx = pac.PacContext(max_elems=n, max_segments=nseg, device=0)
+    try:
+        h = ctx.handle
+        words = (n + 63) // 64
+        k = sum(pac.pac_keep_count(wl.scope_offsets[i + 1] - wl.scope_offsets[i], sp[i]) for i in range(nseg))
+        weights = wl.weights.clone()
+        grads = [g.clone() for g in wl.grads]
+        mask = torch.empty(words, dtype=torch.int64, device=dev)
+        prefix = torch.empty(words, dtype=torch.int32, device=dev)
+        compact = [torch.empty(k, dtype=grads[0].dtype, device=dev) for _ in range(W)]
+        red = torch.empty(k, dtype=grads[0].dtype, device=dev)
+        dense = torch.empty(n, dtype=grads[0].dtype, device=dev)
+
+        def step():
+            nnz = pac.pac_build_mask(h, weights, wl.scope_offsets, sp, mask, prefix)
+            for w in range(W):
+                pac.pac_compress(h, grads[w], mask, prefix, compact[w], nnz)
+            pac.pac_reduce_local(h, compact, red, nnz)
+            pac.pac_decompress(h, red, mask, prefix, dense, nnz)
+
+        step()                                   # eager warm-up: uploads the scope table, one-time set-up
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        torch.cuda.synchronize()
+
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(77)
+        for replay in range(4):
+            # fresh inputs in the captured buffers, written eagerly
+            weights.copy_(torch.randn(n, device=dev, generator=gen) * 0.02)
+            for g in grads:
+                g.copy_(torch.randn(n, device=dev, generator=gen).to(g.dtype))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            got = (mask.clone(), prefix.clone(), red.clone(), dense.clone())
+            mask.zero_(); prefix.zero_(); red.zero_(); dense.zero_()
+            torch.cuda.synchronize()
+            step()                               # the same step, eagerly
+            torch.cuda.synchronize()
+            assert torch.equal(got[0], mask) and torch.equal(got[1], prefix), f"replay {replay}: mask differs"
+            assert torch.equal(got[2].view(torch.int16 if red.dtype == torch.bfloat16 else torch.int32),
+                               red.view(torch.int16 if red.dtype == torch.bfloat16 else torch.int32))
+            assert torch.equal(got[3].view(torch.int16 if red.dtype == torch.bfloat16 else torch.int32),
+                               dense.view(torch.int16 if red.dtype == torch.bfloat16 else torch.int32))
+    finally:
+        ctx.close()
