@@ -8,9 +8,12 @@
  *
  *     pac_build_mask -> pac_compress (once per worker) -> pac_reduce_local -> pac_decompress
  *
+ * and, further down, what the paper puts around them: the Mask Tracker (Sec. III-B), the weight
+ * update of Eq. 1 fused into the decompression, and the ternary payload of Sec. III-D.
+ *
  * Conventions
  *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller owns every data
- *    buffer.  The context owns only scratch (histograms, candidate lists, scan state), sized in
+ *    buffer.  The context owns only scratch (histograms, tile records, scan state), sized in
  *    pac_create; no call on the path allocates.
  *  - Every path call enqueues its kernels on `hip_stream` (a hipStream_t passed as void*; NULL is
  *    the default stream) and returns without synchronising.  Calls on one context must be issued
