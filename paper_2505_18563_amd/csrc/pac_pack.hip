@@ -55,7 +55,7 @@ __device__ __forceinline__ uint16_t elem_of<uint16_t>(const uint4& v, int e) {
 // gather (compress) uses one workgroup per tile, see below.
 constexpr int kPackBlock = 128;
 constexpr int kPackWaves = kPackBlock / 64;
-constexpr int kPackU = 2;
+constexpr int kPackU = 4;   // measured: 2 -> 4 takes 17 % off the bf16 scatter, 12 % off the fp32 one; 8 is slower again
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
