@@ -258,7 +258,7 @@ def main() -> int:
         "step_frac_of_hbm_peak": round(step_alg / step_s / 1e9 / HBM_PEAK_GBPS, 4),
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "roofline": {
-            "kernel": "compress_tile_kernel<unsigned short, 2> (pac_compress)" if wl.dtype == "bf16" else "compress_tile_kernel<unsigned int, 2> (pac_compress)",
+            "kernel": "compress_tile_kernel<unsigned short, 7> (pac_compress)" if wl.dtype == "bf16" else "compress_tile_kernel<unsigned int, 7> (pac_compress)",
             "bound": "hbm",
             "achieved": round(achieved, 2),
             "peak": HBM_PEAK_GBPS,

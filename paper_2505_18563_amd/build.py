@@ -14,6 +14,8 @@ HEADERS = [os.path.join(CSRC, "pac_internal.h"), os.path.join(HERE, "..", "inclu
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off", "-fno-fast-math", "-fno-gpu-flush-denormals-to-zero", "-Wall",
+    # kernels that ask for 8 waves per SIMD only to cap their registers end up bounded by LDS
+    "-Wno-pass-failed",
     # Packed fp32 VALU forms are kept out of the generated code on the test machines.
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
