@@ -16,7 +16,8 @@
  *    buffer.  The context owns only scratch (histograms, tile records, scan state), sized in
  *    pac_create; no call on the path allocates.
  *  - Every path call enqueues its kernels on `hip_stream` (a hipStream_t passed as void*; NULL is
- *    the default stream) and returns without synchronising.  Calls on one context must be issued
+ *    the default stream) and returns without synchronising.  (pac_build_mask runs part of its work
+ *    on a stream of the context, forked from and joined back to `hip_stream` with events.)  Calls on one context must be issued
  *    on one stream at a time: they share the context's scratch.
  *  - A call returns PAC_OK or a negative pac_status; argument errors are found on the host before
  *    anything is launched and leave the outputs untouched.  The text of the last error is kept in

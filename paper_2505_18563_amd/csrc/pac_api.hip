@@ -101,6 +101,9 @@ void free_scratch(pac_ctx* ctx) {
     (void)hipFree(s.match);
     (void)hipFree(s.match_count);
     (void)hipFree(s.tile_state);
+    if (s.side_stream) (void)hipStreamDestroy(s.side_stream);
+    if (s.fork_event) (void)hipEventDestroy(s.fork_event);
+    if (s.join_event) (void)hipEventDestroy(s.join_event);
     for (int i = 0; i < kRing; ++i) {
         if (ctx->h_ring[i]) (void)hipHostFree(ctx->h_ring[i]);
         if (ctx->ring_event[i]) (void)hipEventDestroy(ctx->ring_event[i]);
@@ -191,6 +194,16 @@ pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_
         if (r != hipSuccess) {
             ok = false;
             code = fail(nullptr, PAC_ERR_NOMEM, "pac_create: pinned staging: %s", hipGetErrorString(r));
+        }
+    }
+    if (ok) {
+        // default priority, not synchronising with the NULL stream
+        hipError_t r = hipStreamCreateWithFlags(&s.side_stream, hipStreamNonBlocking);
+        if (r == hipSuccess) r = hipEventCreateWithFlags(&s.fork_event, hipEventDisableTiming);
+        if (r == hipSuccess) r = hipEventCreateWithFlags(&s.join_event, hipEventDisableTiming);
+        if (r != hipSuccess) {
+            ok = false;
+            code = fail(nullptr, PAC_ERR_HIP, "pac_create: side stream: %s", hipGetErrorString(r));
         }
     }
     if (ok) {

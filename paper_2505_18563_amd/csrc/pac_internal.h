@@ -93,6 +93,11 @@ struct MaskScratch {
     uint32_t* match_count;         // [kMatchBlocks] slots used by each workgroup
     unsigned long long cand_cap;   // undecided elements the records may list in total (a test hook lowers it)
     unsigned long long* tile_state; // per scan tile: status and running count of the look-back scan
+    // The small scopes' workgroups only need the weights and emit's zeroed words: they run on a side
+    // stream, next to the kernels that resolve the large scopes, and join before the scan.
+    hipStream_t side_stream;
+    hipEvent_t fork_event;
+    hipEvent_t join_event;
 };
 
 // Launchers (defined in pac_mask.hip / pac_pack.hip).  All enqueue on `stream` and return the

@@ -1238,7 +1238,8 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
     // Pass 0 works from (possibly sampled) histograms; pass 1 repeats the five kernels with full
     // counts if a sampled bracket missed, and returns at once otherwise.
     // (A table with no sampled scope cannot miss: the second round is not even launched.)
-    for (uint32_t pass = 0; pass < (any_sampled ? 2u : 1u); ++pass) {
+    const uint32_t passes = any_sampled ? 2u : 1u;
+    for (uint32_t pass = 0; pass < passes; ++pass) {
         // The sampled pass visits few tiles: no more workgroups than tiles.
         uint32_t grid = hist_grid;
         if (pass == 0) {
@@ -1258,20 +1259,27 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
         const uint32_t emit_grid = pass == 0 || emit_tiles < 2048 ? emit_tiles : 2048u;
         hipLaunchKernelGGL(emit_kernel, dim3(emit_grid), dim3(kEmitBlock), 0, stream, d_weights, n, s.seg, nseg,
                            s.state, s.glob, s.tile_scope, s.kept_above, s.rec, rec_cap, d_mask, pass);
+        if (pass + 1 == passes && max_small != 0) {
+            // after the last emit (it writes the small scopes' words as zero): fork
+            hipError_t r = hipEventRecord(s.fork_event, stream);
+            if (r == hipSuccess) r = hipStreamWaitEvent(s.side_stream, s.fork_event, 0);
+            if (r != hipSuccess) return r;
+            if (max_tiny != 0)
+                hipLaunchKernelGGL((small_scope_kernel<256, kTinyScope>), dim3(nseg), dim3(256),
+                                   (size_t)max_tiny * sizeof(uint32_t), s.side_stream, d_weights, s.seg, d_mask, 0u);
+            if (max_small > kTinyScope)
+                hipLaunchKernelGGL((small_scope_kernel<1024, kSmallScope>), dim3(nseg), dim3(1024),
+                                   (size_t)max_small * sizeof(uint32_t), s.side_stream, d_weights, s.seg, d_mask,
+                                   kTinyScope + 1u);
+            r = hipEventRecord(s.join_event, s.side_stream);
+            if (r != hipSuccess) return r;
+        }
         const uint32_t count_grid = emit_tiles < kCountBlocks ? emit_tiles : kCountBlocks;
         hipLaunchKernelGGL(count1_kernel, dim3(count_grid), dim3(kCountBlock), 0, stream, d_weights, n, s.seg, nseg,
                            s.state, s.glob, s.tile_scope, s.rec, s.hist1, s.kept_above, pass);
         hipLaunchKernelGGL(select1_kernel, dim3(nseg), dim3(kDigit1Bins / 16), 0, stream, s.seg, s.state, s.hist1,
                            s.kept_above, s.glob, pass);
     }
-
-    // after the last emit: these overwrite the small scopes' all-zero words
-    if (max_tiny != 0)
-        hipLaunchKernelGGL((small_scope_kernel<256, kTinyScope>), dim3(nseg), dim3(256),
-                           (size_t)max_tiny * sizeof(uint32_t), stream, d_weights, s.seg, d_mask, 0u);
-    if (max_small > kTinyScope)
-        hipLaunchKernelGGL((small_scope_kernel<1024, kSmallScope>), dim3(nseg), dim3(1024),
-                           (size_t)max_small * sizeof(uint32_t), stream, d_weights, s.seg, d_mask, kTinyScope + 1u);
 
     hipLaunchKernelGGL(compact2_kernel, dim3(kMatchBlocks), dim3(kListBlock), 0, stream, d_weights, n, s.seg, nseg,
                        s.state, s.glob, s.tile_scope, s.rec, s.match, s.match_count);
@@ -1280,6 +1288,10 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
     const uint32_t scan_tiles = div_up_u64(words, kScanTile);
     hipLaunchKernelGGL(fixup_kernel, dim3(kMatchBlocks), dim3(kListBlock), 0, stream, d_weights, n, s.seg, nseg,
                        s.state, s.tile_scope, s.rec, d_mask, s.tile_state, scan_tiles);
+    if (max_small != 0) {   // join: the scan reads the small scopes' words
+        hipError_t r = hipStreamWaitEvent(stream, s.join_event, 0);
+        if (r != hipSuccess) return r;
+    }
     hipLaunchKernelGGL(scan_lookback_kernel, dim3(scan_tiles), dim3(kScanBlock), 0, stream, d_mask, words,
                        s.tile_state, s.glob, d_prefix, static_cast<u64*>(nullptr));
     return hipGetLastError();
