@@ -68,3 +68,38 @@ def test_step_replays_from_a_graph(config_id):
                                dense.view(torch.int16 if red.dtype == torch.bfloat16 else torch.int32))
     finally:
         ctx.close()
+
+
+def test_two_contexts_on_two_streams_do_not_interfere():
+    """Two contexts, each on a stream of its own, interleaved from the host: same results as one after the other."""
+    import paper_2505_18563_amd as pac
+    dev = torch.device("cuda", 0)
+    wls = [make_workload(2, device=dev), make_workload(1, device=dev)]
+    ctxs = [pac.PacContext(max_elems=wl.n, max_segments=len(wl.scope_offsets) - 1, device=0) for wl in wls]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    try:
+        def run(i, stream):
+            wl, ctx = wls[i], ctxs[i]
+            sp = wl.sparsity_at(0)
+            mask, prefix, k = ctx.build_mask(wl.weights, wl.scope_offsets, sp, stream=stream)
+            compact = [ctx.compress(g, mask, prefix, k, stream=stream) for g in wl.grads]
+            red = ctx.reduce_local(compact, k, stream=stream)
+            return mask, prefix, ctx.decompress(red, mask, prefix, wl.n, k, stream=stream)
+
+        torch.cuda.synchronize()
+        ref = [run(i, None) for i in range(2)]
+        torch.cuda.synchronize()
+        for _ in range(5):
+            for s in streams:
+                s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(streams[0]):
+                a = run(0, streams[0])
+            with torch.cuda.stream(streams[1]):
+                b = run(1, streams[1])
+            torch.cuda.synchronize()
+            for got, want in ((a, ref[0]), (b, ref[1])):
+                assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
+                assert torch.equal(got[2].view(torch.int32), want[2].view(torch.int32))
+    finally:
+        for c in ctxs:
+            c.close()
