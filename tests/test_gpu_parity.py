@@ -141,6 +141,22 @@ def test_build_mask_many_small_segments(ctx):
     check_mask(ctx, w, off, sp, "400 small scopes")
 
 
+def test_build_mask_thousands_of_scopes(pac):
+    """5000 prune scopes of 0..3000 elements plus a few large ones in between."""
+    rng = np.random.default_rng(25)
+    sizes = rng.integers(0, 3000, size=5000)
+    sizes[[7, 1234, 4000]] = [200001, 50000, 33000]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    c = pac.PacContext(max_elems=int(off[-1]), max_segments=5000, device=0)
+    try:
+        for kind in ("gauss", "ties"):
+            w = weights_of(kind, int(off[-1]), rng)
+            sp = rng.choice([0.0, 0.5, 0.9, 1.0], size=sizes.size, p=[0.05, 0.45, 0.45, 0.05])
+            check_mask(c, w, off, sp, f"5000 scopes {kind}")
+    finally:
+        c.close()
+
+
 @pytest.mark.parametrize("capacity", [0, 1000, 4000])
 def test_build_mask_tiles_whose_undecided_elements_are_not_listed(pac, capacity):
     """A lowered listing capacity leaves most or all 4096-element tiles without a list of their undecided
