@@ -55,6 +55,19 @@ __device__ __forceinline__ bool tile_sampled(uint32_t t, uint32_t m) {
     return (t & (m - 1)) == (hash32(group) & (m - 1));
 }
 
+// The first tile >= t that tile_sampled() accepts at stride m.
+__device__ __forceinline__ uint32_t next_sampled(uint32_t t, uint32_t m) {
+    if (m <= 1) return t;
+    const uint32_t shift = 31 - __clz((int)m);
+    uint32_t group = t >> shift;
+    uint32_t cand = (group << shift) + (hash32(group) & (m - 1));
+    if (cand < t) {
+        ++group;
+        cand = (group << shift) + (hash32(group) & (m - 1));
+    }
+    return cand;
+}
+
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
 __device__ __forceinline__ uint32_t lanes_below(u64 m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
@@ -178,7 +191,20 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
                 cur_end = s_end;
                 cur_stride = raw_stride;
             }
-            if (pass == 0 && !tile_sampled(t, raw_stride)) continue;
+            if (pass == 0 && raw_stride > 1) {
+                // Go straight to the scope's next sampled tile.  Every wave of the chip runs this
+                // loop, and a compute unit issues one scalar instruction per clock for all of its
+                // waves together, so stepping over the unsampled tiles one by one would cost more
+                // than the sampled tiles' loads.
+                const uint32_t next = next_sampled(t, raw_stride);
+                if (next != t) {
+                    // The tiles before cur_end / kHistTile are whole tiles of this scope.  A ragged
+                    // last tile is its own "first tile not wholly inside": step past it.
+                    const uint32_t past_whole = cur_end / kHistTile;
+                    t = max(min(next, past_whole), t + 1) - 1;   // the loop adds the 1 back
+                    continue;
+                }
+            }
             if (VEC && b - a == kHistTile) {
                 const u32x4* p = reinterpret_cast<const u32x4*>(w + a) + threadIdx.x;
                 u32x4 v[kHistLoads];
