@@ -79,7 +79,7 @@ bool is_aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t
 uint32_t elem_size(pac_dtype dt) { return dt == PAC_F32 ? 4u : 2u; }
 
 // Stride of the sampled histogram pass over one prune scope: scopes below 4M elements are counted
-// in full; larger ones keep at least about 2M sampled elements, at most one 16384-element tile in 16.
+// in full; larger ones keep at least about 2M sampled elements, at most one 16384-element tile in 64.
 // 0 marks a small scope.
 uint32_t sample_stride(uint64_t len) {
     if (len <= pac::kSmallScope) return 0;   // small scope: resolved by one workgroup, outside the histogram passes

@@ -50,7 +50,7 @@ struct SegState {
     uint32_t pad[2];
 };
 
-constexpr uint32_t kMaxSampleStride = 16;  // largest SegDesc::stride (power of two)
+constexpr uint32_t kMaxSampleStride = 64;  // largest SegDesc::stride (power of two)
 
 // Scopes of up to this many elements (norm and bias vectors, small kernels) are resolved by one
 // workgroup each with the keys held in LDS: exact whatever the ties, and no per-scope traffic in
