@@ -14,7 +14,7 @@ namespace {
 
 constexpr int kRing = 4;               // pinned staging slots for the segment table
 constexpr uint32_t kMaxSegments = 65535;   // scopes index a grid dimension
-constexpr uint64_t kScanTileWords = 2048;  // not larger than the scan kernel's tile
+constexpr uint64_t kScanTileWords = 2048;  // not larger than the smallest tile the scan kernel uses
 
 thread_local char g_create_error[256] = "";
 

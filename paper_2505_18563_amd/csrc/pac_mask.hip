@@ -1103,11 +1103,11 @@ __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restri
 // prefix.  Status and value share one 64-bit word, read and written with device-scope atomics, so
 // no other data needs ordering across the XCDs' L2 caches.  The wait for a predecessor is bounded:
 // a workgroup that gives up raises `scan_stalled` and finishes (with wrong offsets) rather than spin.
+// The tile size follows the size of the mask (scan_iters_for): a tile per workgroup must be small
+// enough for the tiles to fill the chip, and large enough that the look-back chain stays short.
 constexpr int kScanBlock = 1024;
 constexpr int kScanWaves = kScanBlock / 64;
-constexpr uint32_t kScanIters = 16;                                  // 16-byte loads per lane
-constexpr uint32_t kScanWaveWords = 64 * 2 * kScanIters;             // 2048 words per wave
-constexpr uint32_t kScanTile = kScanWaves * kScanWaveWords;          // 32768 words
+constexpr uint32_t scan_tile_words(uint32_t iters) { return kScanWaves * 64u * 2u * iters; }   // iters 16-byte loads per lane
 constexpr u64 kTileAggregate = 1ull << 32;   // value = bits in this tile
 constexpr u64 kTileInclusive = 2ull << 32;   // value = bits in this tile and all before it
 constexpr uint32_t kScanSpinLimit = 1u << 22;
@@ -1119,6 +1119,7 @@ __device__ __forceinline__ void tile_store(u64* p, u64 v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+template <uint32_t kScanIters>
 __global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __restrict__ mask, uint32_t words,
                                                                    u64* __restrict__ tile_state, Globals* glob,
                                                                    uint32_t* __restrict__ prefix,
@@ -1130,8 +1131,9 @@ __global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __
     __syncthreads();
     const uint32_t tile = sh_tile;
     const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+    constexpr uint32_t kScanWaveWords = 64 * 2 * kScanIters, kScanTile = kScanWaves * kScanWaveWords;
 
-    // A lane owns two consecutive words per iteration (one 16-byte load); a wave 2048 consecutive words.
+    // A lane owns two consecutive words per iteration (one 16-byte load); a wave kScanWaveWords consecutive words.
     const u64 wave_first = (u64)tile * kScanTile + wave * kScanWaveWords;
     uint32_t pp[kScanIters];   // popcounts of the lane's two words, packed: low byte first word, next byte second
 #pragma unroll
@@ -1227,6 +1229,29 @@ __global__ void scan_reset_kernel(u64* __restrict__ tile_state, uint32_t tiles, 
 
 inline uint32_t div_up_u64(u64 a, u64 b) { return (uint32_t)((a + b - 1) / b); }
 
+// 16-byte loads per lane of the scan for a mask of `words` words (measured: 4096-word tiles up to
+// 32M elements, 8192-word tiles up to 256M, 32768-word tiles above).
+inline uint32_t scan_iters_for(uint32_t words) { return words <= (1u << 19) ? 2u : words <= (1u << 22) ? 4u : 16u; }
+inline uint32_t scan_tiles_for(uint32_t words) { return div_up_u64(words, scan_tile_words(scan_iters_for(words))); }
+
+inline void launch_scan(const u64* d_mask, uint32_t words, u64* tile_state, Globals* glob, uint32_t* d_prefix,
+                        u64* d_total_out, hipStream_t stream) {
+    const uint32_t tiles = scan_tiles_for(words);
+    switch (scan_iters_for(words)) {
+        case 2:
+            hipLaunchKernelGGL((scan_lookback_kernel<2>), dim3(tiles), dim3(kScanBlock), 0, stream, d_mask, words,
+                               tile_state, glob, d_prefix, d_total_out);
+            break;
+        case 4:
+            hipLaunchKernelGGL((scan_lookback_kernel<4>), dim3(tiles), dim3(kScanBlock), 0, stream, d_mask, words,
+                               tile_state, glob, d_prefix, d_total_out);
+            break;
+        default:
+            hipLaunchKernelGGL((scan_lookback_kernel<16>), dim3(tiles), dim3(kScanBlock), 0, stream, d_mask, words,
+                               tile_state, glob, d_prefix, d_total_out);
+    }
+}
+
 // Workgroups of a persistent kernel that fit on the device at once.
 template <typename K>
 uint32_t resident_blocks(K kernel, int block, int num_cu, uint32_t fallback_per_cu) {
@@ -1311,26 +1336,24 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
                        s.state, s.glob, s.tile_scope, s.rec, s.match, s.match_count);
     hipLaunchKernelGGL(final_kernel, dim3(nseg), dim3(kFinalBlock), 0, stream, d_weights, s.seg, s.state, s.glob,
                        s.match, s.match_count);
-    const uint32_t scan_tiles = div_up_u64(words, kScanTile);
+    const uint32_t scan_tiles = scan_tiles_for(words);
     hipLaunchKernelGGL(fixup_kernel, dim3(kMatchBlocks), dim3(kListBlock), 0, stream, d_weights, n, s.seg, nseg,
                        s.state, s.tile_scope, s.rec, d_mask, s.tile_state, scan_tiles);
     if (max_small != 0) {   // join: the scan reads the small scopes' words
         hipError_t r = hipStreamWaitEvent(stream, s.join_event, 0);
         if (r != hipSuccess) return r;
     }
-    hipLaunchKernelGGL(scan_lookback_kernel, dim3(scan_tiles), dim3(kScanBlock), 0, stream, d_mask, words,
-                       s.tile_state, s.glob, d_prefix, static_cast<u64*>(nullptr));
+    launch_scan(d_mask, words, s.tile_state, s.glob, d_prefix, static_cast<u64*>(nullptr), stream);
     return hipGetLastError();
 }
 
 hipError_t launch_prefix_scan(const MaskScratch& s, const unsigned long long* d_mask, uint32_t words,
                               uint32_t* d_prefix, unsigned long long* d_total_out, hipStream_t stream) {
     if (words == 0) return hipSuccess;
-    const uint32_t scan_tiles = div_up_u64(words, kScanTile);
+    const uint32_t scan_tiles = scan_tiles_for(words);
     hipLaunchKernelGGL(scan_reset_kernel, dim3(div_up_u64(scan_tiles + 1, 256)), dim3(256), 0, stream, s.tile_state,
                        scan_tiles, s.glob);
-    hipLaunchKernelGGL(scan_lookback_kernel, dim3(scan_tiles), dim3(kScanBlock), 0, stream, d_mask, words,
-                       s.tile_state, s.glob, d_prefix, d_total_out);
+    launch_scan(d_mask, words, s.tile_state, s.glob, d_prefix, d_total_out, stream);
     return hipGetLastError();
 }
 
