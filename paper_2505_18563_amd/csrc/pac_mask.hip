@@ -978,7 +978,21 @@ __global__ __launch_bounds__(kSmallBlock) void small_scope_kernel(const float* _
     const uint32_t begin = d.begin, end = d.end, len = end - begin, k = d.k;
     if (len < min_len || len > kMaxLen) return;            // the other size class
     if (len == 0 || k == 0) return;                        // nothing kept: emit wrote the zeros
-    for (uint32_t j = threadIdx.x; j < len; j += kSmallBlock) keys[j] = key_of_bits(__float_as_uint(w[begin + j]));
+    // eight loads in flight per thread: one load per trip would make a long scope wait for memory
+    // thirty-two times in a row
+    for (uint32_t j0 = threadIdx.x; j0 < len; j0 += kSmallBlock * 8) {
+        uint32_t v[8];
+#pragma unroll
+        for (uint32_t q = 0; q < 8; ++q) {
+            const uint32_t j = min(j0 + q * kSmallBlock, len - 1u);   // clamped, not branched: the loads stay together
+            v[q] = __float_as_uint(w[begin + j]);
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < 8; ++q) {
+            const uint32_t j = j0 + q * kSmallBlock;
+            if (j < len) keys[j] = key_of_bits(v[q]);
+        }
+    }
     if (threadIdx.x == 0) { found[0] = 0; found[1] = 0; }
     __syncthreads();
 
