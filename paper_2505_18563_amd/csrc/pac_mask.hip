@@ -147,6 +147,21 @@ __device__ __forceinline__ void flush_hist0(uint32_t* lds, uint32_t* __restrict_
     __syncthreads();
 }
 
+// Counts the elements [from, to) of w, from < to, into the LDS histogram, the workgroup's threads
+// striding over them with eight loads in flight each (indices clamped, not branched, so that the
+// loads are issued together: one load per trip would wait for memory once per 1024 elements).
+__device__ __forceinline__ void hist0_range(const float* __restrict__ w, u64 from, u64 to, uint32_t* lds) {
+    constexpr uint32_t kFlight = 8;
+    for (u64 i0 = from + threadIdx.x; i0 < to; i0 += (u64)kHistBlock * kFlight) {
+        uint32_t v[kFlight];
+#pragma unroll
+        for (uint32_t q = 0; q < kFlight; ++q) v[q] = __float_as_uint(w[min(i0 + q * kHistBlock, to - 1)]);
+#pragma unroll
+        for (uint32_t q = 0; q < kFlight; ++q)
+            if (i0 + q * kHistBlock < to) atomicAdd(&lds[digit0_of(key_of_bits(v[q]))], 1u);
+    }
+}
+
 template <bool VEC>
 __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restrict__ w, uint32_t n,
                                                            const SegDesc* __restrict__ seg, uint32_t nseg,
@@ -218,8 +233,7 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
                     atomicAdd(&lds[digit0_of(key_of_bits(v[u].w))], 1u);
                 }
             } else {
-                for (u64 i = (u64)a + threadIdx.x; i < b; i += kHistBlock)
-                    atomicAdd(&lds[digit0_of(key_of_bits(__float_as_uint(w[i])))], 1u);
+                hist0_range(w, a, b, lds);
             }
         } else {
             // The tile crosses scope boundaries: one sub-range per scope, each under its own scope's
@@ -237,8 +251,7 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
                             cur_end = se;
                             cur_stride = sstride;
                         }
-                        for (u64 i = (u64)pos + threadIdx.x; i < upto; i += kHistBlock)
-                            atomicAdd(&lds[digit0_of(key_of_bits(__float_as_uint(w[i])))], 1u);
+                        hist0_range(w, pos, upto, lds);
                     }
                     pos = upto;
                 }
