@@ -805,9 +805,12 @@ __global__ __launch_bounds__(kCountBlock) void count1_kernel(const float* __rest
             if (cur != kNone) flush();
             cur = s_round;
         }
-        const uint32_t t0 = t + wave * 64;
+        // the round's tiles in equal shares (of at most 64) over the waves, so that a short round
+        // still occupies all of them
+        const uint32_t share = (r_end - t + kWaves - 1) / kWaves;
+        const uint32_t t0 = t + wave * share;
         if (t0 < r_end) {
-            visit_tiles(w, n, seg, nseg, state, tile_scope, rec, t0, r_end, ws[wave],
+            visit_tiles(w, n, seg, nseg, state, tile_scope, rec, t0, min(r_end, t0 + share), ws[wave],
                 [&](uint32_t, u64 hdr, uint32_t s0, bool single) {
                     // kept elements of a tile inside one scope (emit counted the others itself)
                     const uint32_t kept = (uint32_t)(hdr >> 32);
