@@ -45,6 +45,8 @@ def parse_args():
     ap.add_argument("--cpu-sample-elems", type=int, default=1 << 28)
     ap.add_argument("--no-around", action="store_true",
                     help="skip the timings of the calls around the hot path (Mask Tracker, fused update)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one whole step in a HIP graph and time its replays (reported as graph_replay_step)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed loop: a kernel of known traffic "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -204,6 +206,22 @@ def main() -> int:
     pac.pac_build_mask(h, wl.weights, wl.scope_offsets, sp0, mask, prefix)
     cached_ms = time_call(cached_mask_step)
 
+    # The whole step (mask build included) replayed from a HIP graph: what is left of the launch
+    # overhead on the small, launch-bound workloads.
+    graph_ms = None
+    if args.graph:
+        def whole_step():
+            pac.pac_build_mask(h, wl.weights, wl.scope_offsets, sp0, mask, prefix)
+            cached_mask_step()
+        whole_step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            whole_step()
+        torch.cuda.synchronize()
+        graph_ms = time_call(graph.replay, reps=20)
+        del graph
+
     # Calls around the hot path (Mask Tracker, fused weight update): timed on the same workload,
     # outside the timed region, reported with their own algorithmic bytes.
     around = {}
@@ -282,6 +300,9 @@ def main() -> int:
             "avg_launch_ms": round(compress_ms, 5),
         },
     }
+    if graph_ms is not None:
+        result["graph_replay_step"] = {"ms": round(graph_ms, 4), "value": round(W * n * e / (graph_ms * 1e-3) / 1e9, 2),
+                                       "unit": "GB/s", "note": "one whole step captured in a HIP graph, 20 replays"}
     if around:
         result["around_the_path"] = around
     if not args.no_cpu_baseline:
