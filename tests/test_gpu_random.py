@@ -79,3 +79,97 @@ def test_random_tables_and_values(seed):
             assert np.array_equal(dense.cpu().numpy().view(np.uint32), ed.view(np.uint32)), f"case {case}: scatter"
     finally:
         ctx.close()
+
+
+def _bits(t):
+    if t.dtype == torch.float32:
+        return t.cpu().numpy().view(np.uint32)
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _device_view(a_f32, bf16, shift):
+    """Device tensor with the values of a_f32 (rounded to bf16 if asked) whose data pointer lies `shift`
+    elements past an aligned allocation, and the host array that the oracle gets."""
+    if bf16:
+        u = oracle.f32_to_bf16(a_f32)
+        base = torch.zeros(u.size + 8, dtype=torch.int16, device="cuda")
+        base[shift:shift + u.size] = torch.from_numpy(u.view(np.int16)).cuda()
+        return base[shift:shift + u.size].view(torch.bfloat16), u
+    base = torch.zeros(a_f32.size + 8, dtype=torch.float32, device="cuda")
+    base[shift:shift + a_f32.size] = torch.from_numpy(a_f32).cuda()
+    return base[shift:shift + a_f32.size], a_f32
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_payloads_and_alignments(seed):
+    """mask_from_nonzero -> compress x W -> reduce_local -> decompress / decompress_update with random length,
+    density, payload type, worker count and element misalignment of every buffer; guard elements around the
+    outputs must keep their values."""
+    import paper_2505_18563_amd as pac
+    rng = np.random.default_rng(seed)
+    ctx = pac.PacContext(max_elems=1 << 23, max_segments=8, device=0)
+    h = ctx.handle
+    try:
+        for case in range(40):
+            n = int(rng.choice([rng.integers(1, 300), rng.integers(1, 70_000), rng.integers(1, 3_000_000)]))
+            bf16 = bool(rng.integers(0, 2))
+            dt = oracle.BF16 if bf16 else oracle.F32
+            dens = float(rng.choice([0.0, 1.0, 0.1, 0.5, rng.random()]))
+            W = int(rng.choice([1, 2, 3, 8, 16, 33]))
+            shift = int(rng.choice([0, 0, 1, 3, 4]))
+            print(f"[random] seed={seed} case={case} n={n} bf16={bf16} density={dens:.3f} W={W} shift={shift}", flush=True)
+            keep = rng.random(n) < dens
+            vals = np.where(keep, rng.standard_normal(n).astype(np.float32) + 3.0, 0).astype(np.float32)
+            vt, vhost = _device_view(vals, bf16, shift)
+            em, ep, nnz = oracle.mask_from_nonzero(vhost, dt)
+            words = (n + 63) // 64
+            m = torch.empty(words, dtype=torch.int64, device="cuda")
+            p = torch.empty(words, dtype=torch.int32, device="cuda")
+            nz = torch.zeros(1, dtype=torch.int64, device="cuda")
+            pac.pac_mask_from_nonzero(h, vt, m, p, nz)
+            torch.cuda.synchronize()
+            assert int(nz.item()) == nnz
+            assert np.array_equal(m.cpu().numpy().view(np.uint64), em), f"case {case}: mask of non-zeros"
+            assert np.array_equal(p.cpu().numpy().view(np.uint32), ep), f"case {case}: prefix"
+
+            comps, ecomps = [], []
+            for w in range(W):
+                g = rng.standard_normal(n).astype(np.float32)
+                gt, ghost = _device_view(g, bf16, int(rng.choice([0, shift])))
+                guard = torch.full((nnz + 8,), 7, dtype=gt.dtype, device="cuda")
+                osh = int(rng.choice([0, 1, 2]))
+                out = guard[osh:osh + nnz]
+                pac.pac_compress(h, gt, m, p, out, nnz)
+                ec = oracle.compress(ghost, em, nnz, dt)
+                torch.cuda.synchronize()
+                assert np.array_equal(_bits(out), ec.view(_bits(out).dtype)), f"case {case}: gather, worker {w}"
+                assert bool((guard[:osh].float() == 7).all()) and bool((guard[osh + nnz:].float() == 7).all()), \
+                    f"case {case}: gather wrote outside its buffer"
+                comps.append(out)
+                ecomps.append(ec)
+
+            red = torch.empty(nnz, dtype=comps[0].dtype, device="cuda")
+            pac.pac_reduce_local(h, comps, red, nnz)
+            er = oracle.reduce_local(ecomps, dt)
+            torch.cuda.synchronize()
+            assert np.array_equal(_bits(red), er.view(_bits(red).dtype)), f"case {case}: sum"
+
+            guard = torch.full((n + 8,), 5, dtype=red.dtype, device="cuda")
+            dsh = int(rng.choice([0, shift]))
+            dense = guard[dsh:dsh + n]
+            pac.pac_decompress(h, red, m, p, dense, nnz)
+            ed = oracle.decompress(er, em, n, dt)
+            torch.cuda.synchronize()
+            assert np.array_equal(_bits(dense), ed.view(_bits(dense).dtype)), f"case {case}: scatter"
+            assert bool((guard[:dsh].float() == 5).all()) and bool((guard[dsh + n:].float() == 5).all()), \
+                f"case {case}: scatter wrote outside its buffer"
+
+            x = rng.standard_normal(n).astype(np.float32)
+            xt = torch.from_numpy(x).cuda()
+            alpha = float(np.float32(rng.random() * 0.1))
+            pac.pac_decompress_update(h, red, m, p, alpha, xt, nnz)
+            ex = oracle.decompress_update(er, em, x, alpha, dt)
+            torch.cuda.synchronize()
+            assert np.array_equal(xt.cpu().numpy().view(np.uint32), ex.view(np.uint32)), f"case {case}: fused update"
+    finally:
+        ctx.close()
