@@ -17,11 +17,15 @@
  *    pac_create; no call on the path allocates.
  *  - Every path call enqueues its kernels on `hip_stream` (a hipStream_t passed as void*; NULL is
  *    the default stream) and returns without synchronising.  (pac_build_mask runs part of its work
- *    on a stream of the context, forked from and joined back to `hip_stream` with events.)  Calls on one context must be issued
- *    on one stream at a time: they share the context's scratch.
+ *    on a stream of the context, forked from and joined back to `hip_stream` with events; see there
+ *    for the one case in which it copies a scope table to the device first.)  Calls on one context
+ *    must be issued on one stream at a time: they share the context's scratch.
  *  - A call returns PAC_OK or a negative pac_status; argument errors are found on the host before
  *    anything is launched and leave the outputs untouched.  The text of the last error is kept in
  *    the context (pac_last_error).  Nothing throws or aborts.
+ *  - What only the device can see (a count that does not match the mask, a bounded wait that gave up)
+ *    cannot be returned by a call that does not wait for the device: the kernels raise bits in a status
+ *    word of the context, which stays as it is until pac_device_status reads and clears it.
  *  - Layout: bit b of mask word j stands for flat element 64*j + b; bits at or beyond n in the last
  *    word are zero.  prefix[j] is the number of set bits in words 0..j-1 over the whole flat set,
  *    so the element at set bit b of word j lives in compact slot
@@ -46,7 +50,8 @@ enum {
     PAC_ERR_ARG = -1,   /* NULL pointer, bad dtype, bad segment table                         */
     PAC_ERR_ALIGN = -2, /* pointer not aligned to its element size                            */
     PAC_ERR_RANGE = -3, /* n >= 2^32 or > context capacity, sparsity outside [0,1], W out of range */
-    PAC_ERR_COUNT = -4, /* nnz passed does not fit n                                          */
+    PAC_ERR_COUNT = -4, /* nnz passed exceeds n (a count that disagrees with the mask itself is only
+                           visible on the device: PAC_DEV_COUNT_MISMATCH)                          */
     PAC_ERR_HIP = -5,   /* a HIP runtime call failed; pac_last_error holds its text           */
     PAC_ERR_NOMEM = -6  /* scratch allocation failed in pac_create                            */
 };
@@ -54,8 +59,25 @@ enum {
 typedef enum { PAC_F32 = 0, PAC_BF16 = 1 } pac_dtype;
 
 #define PAC_MAX_WORKERS 64u
+#define PAC_TABLE_SLOTS 4u
 
 typedef struct pac_ctx pac_ctx;
+
+/* Bits of the context's device status word (pac_device_status).  The low byte holds conditions
+ * under which an output is NOT what this header promises; the bits above it only tell which of the
+ * slower, equally exact code paths ran. */
+enum {
+    PAC_DEV_SCAN_STALLED = 0x01,    /* the prefix scan's bounded wait for an earlier tile gave up: d_prefix
+                                       (and a count derived from it) is wrong                              */
+    PAC_DEV_COUNT_MISMATCH = 0x02,  /* the number of set mask bits is not the nnz the call was given (or, in
+                                       pac_build_mask, not the sum of the scopes' keep counts)             */
+    PAC_DEV_META_MISMATCH = 0x04,   /* mask, prefix and nnz passed to a gather / scatter do not fit together:
+                                       the tile was skipped (gather) or zero-filled (scatter)              */
+    PAC_DEV_RETRY_TAKEN = 0x100,    /* a sampled threshold bracket missed and pac_build_mask ran its
+                                       full-count pass                                                     */
+    PAC_DEV_SLOW_PATH = 0x200       /* very many equal magnitudes: pac_build_mask resolved a scope from its
+                                       weights instead of its candidate lists                              */
+};
 
 /* Create a context on HIP device `hip_device` able to build masks over up to `max_elems` flat
  * elements split into up to `max_segments` prune scopes.  Allocates all scratch.  *out is NULL on
@@ -68,6 +90,15 @@ pac_status pac_destroy(pac_ctx* ctx);
 /* Text of the last error of this context ("" if none).  Owned by the context.  With ctx == NULL,
  * the text of the last failed pac_create of this thread. */
 const char* pac_last_error(const pac_ctx* ctx);
+
+/* Reads the context's device status word (PAC_DEV_* bits, raised by the kernels of earlier calls on
+ * this context and sticky until cleared).  Enqueued on `hip_stream` behind those calls.
+ *   d_flags_out (DEVICE uint32, may be NULL): receives the word, in stream order; no host wait.
+ *   h_flags_out (HOST uint32, may be NULL): receives the word; the call then waits for the stream.
+ *   clear != 0: the word is reset to zero by the same read.
+ * With both pointers NULL and clear == 0 the call does nothing. */
+pac_status pac_device_status(pac_ctx* ctx, uint32_t* d_flags_out, uint32_t* h_flags_out, int clear,
+                             void* hip_stream);
 
 /* Keep count of one prune scope of n elements at a target sparsity (the pruning ratio of Alg. 1):
  * k = ceil((1 - s) * n), evaluated in integers with s rounded to the nearest 1e-6.  Pure host
@@ -90,7 +121,17 @@ uint64_t pac_mask_words(uint64_t n);
  *
  * Writes d_mask[ceil(n/64)] and d_prefix[ceil(n/64)]; *h_nnz_out (may be NULL) receives
  * sum_s k_s, which is known on the host without waiting for the device.  n = 0 is allowed
- * (nothing is written). */
+ * (nothing is written).
+ *
+ * Scope tables: the context keeps the last PAC_TABLE_SLOTS distinct (offsets, sparsity) tables it was
+ * given resident on the device.  A call whose table is among them enqueues kernels only.  A call with
+ * a new table first copies it to the device (an asynchronous copy from pinned memory of the context,
+ * on `hip_stream`; it replaces the least recently used table, and waits on the host only if that
+ * slot's previous upload, many calls ago, has still not run).  While `hip_stream` is being captured
+ * into a graph a new table is refused with PAC_ERR_ARG: run the call once outside the capture first;
+ * a table used under capture then stays resident for the life of the context.
+ * Device-side checks: PAC_DEV_COUNT_MISMATCH if the mask it wrote does not hold sum_s k_s bits,
+ * PAC_DEV_SCAN_STALLED, and the two informational bits. */
 pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n,
                           const uint64_t* h_seg_offsets, uint32_t nseg, const double* h_sparsity,
                           uint64_t* d_mask, uint32_t* d_prefix, uint64_t* h_nnz_out,
@@ -100,7 +141,8 @@ pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n,
  * sparse gradient into a low-dimensional dense tensor; Alg. 1 compress(update)):
  * d_compact[slot(i)] = d_grad[i] for every set bit i, bit-exact copies, ascending flat index.
  * nnz must be the number of set bits (the value pac_build_mask returned); the kernel never writes
- * at or beyond d_compact[nnz]. */
+ * at or beyond d_compact[nnz].  A different nnz raises PAC_DEV_COUNT_MISMATCH, metadata that does not
+ * fit together PAC_DEV_META_MISMATCH, in the context's device status word. */
 pac_status pac_compress(pac_ctx* ctx, const void* d_grad, pac_dtype dtype, uint64_t n,
                         const uint64_t* d_mask, const uint32_t* d_prefix,
                         void* d_compact, uint64_t nnz, void* hip_stream);
@@ -116,7 +158,7 @@ pac_status pac_reduce_local(pac_ctx* ctx, const void* const* h_d_compact, uint32
 
 /* (4) Decompress (paper Eq. 2 read as a selection): d_dense_out[i] = d_compact[slot(i)] where the
  * mask bit is set, the all-zero bit pattern (+0.0) elsewhere.  Every one of the n outputs is
- * written.  No read at or beyond d_compact[nnz]. */
+ * written.  No read at or beyond d_compact[nnz].  Device-side checks as in pac_compress. */
 pac_status pac_decompress(pac_ctx* ctx, const void* d_compact, pac_dtype dtype, uint64_t nnz,
                           const uint64_t* d_mask, const uint32_t* d_prefix,
                           void* d_dense_out, uint64_t n, void* hip_stream);
@@ -126,7 +168,7 @@ pac_status pac_decompress(pac_ctx* ctx, const void* d_compact, pac_dtype dtype, 
  * ------------------------------------------------------------------------------------------ */
 
 /* Mask of the non-zero elements of a flat tensor: the (Weight != 0) of paper Eq. 2, which is how the
- * Mask Tracker (Sec. III-B "Mask Tracker mechanism") reads the sparsity pattern off a flattened
+ * Mask Tracker (Sec. III-B, Mask Tracker paragraph) reads the sparsity pattern off a flattened
  * bucket.  Bit i is set iff d_values[i] != 0 as an IEEE comparison (both zeros are zero; NaN and
  * denormals are not).  Writes d_mask[ceil(n/64)] (bits >= n zero), d_prefix[ceil(n/64)] and, if
  * d_nnz_out is not NULL, the number of set bits to that DEVICE location (the count depends on the
@@ -142,11 +184,12 @@ pac_status pac_mask_from_nonzero(pac_ctx* ctx, const void* d_values, pac_dtype d
 pac_status pac_mask_equal(pac_ctx* ctx, const uint64_t* d_mask_a, const uint64_t* d_mask_b, uint64_t n,
                           uint64_t* d_diff_bits_out, void* hip_stream);
 
-/* Mask Tracker bookkeeping (Sec. III-B; Alg. 1 "Update sparse mask using Mask Tracker" / "if mask is
- * stable"): keeps the previous iteration's mask on the device and counts consecutive comparisons
- * that found no difference.  The pattern is "stable" once that count reaches `patience` (the paper
- * says "multiple iterations" and gives no number: the caller chooses, >= 1).  The first mask a
- * tracker sees, and a mask of another length n, count as a change.
+/* Mask Tracker bookkeeping (Sec. III-B; Alg. 1, the mask-update step and the stability test that
+ * chooses between the two synchronisations): keeps the previous iteration's mask on the device and
+ * counts consecutive comparisons that found no difference.  The pattern counts as stable once that
+ * count reaches `patience` (the paper asks for an unchanged pattern over several iterations without
+ * giving a number: the caller chooses, >= 1).  The first mask a tracker sees, and a mask of another
+ * length n, count as a change.
  * pac_tracker_update enqueues compare + copy on the stream and writes {unchanged, stable} to
  * d_state_out (DEVICE uint32[2], may be NULL).  The caller decides between the compressed and the
  * dense synchronisation from that state (for the dense one, pac_reduce_local sums W dense buffers
@@ -169,7 +212,7 @@ pac_status pac_decompress_update(pac_ctx* ctx, const void* d_reduced, pac_dtype 
                                  float* d_weights, uint64_t n, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------
- * Ternary payload (paper Sec. III-D "Pruning with Gradient Quantization": ternarize(g) quantises
+ * Ternary payload (paper Sec. III-D: ternarize(g) quantises
  * the gradient at random into {-1, 0, +1} times a scale, unbiased in expectation, Eq. 3).  The
  * quantiser is the TernGrad one the section names: with a scale s >= max|g| shared by the workers,
  * element -> s * sign(g) * b, b ~ Bernoulli(|g| / s).  It is applied to the compact buffers; the
@@ -204,6 +247,12 @@ pac_status pac_ternary_reduce_local(pac_ctx* ctx, const uint8_t* const* h_d_pack
  * elements do not fit are re-read from the weights by the later passes; results are identical.
  * Exists so that tests can reach that branch with small inputs. */
 pac_status pac_debug_set_candidate_capacity(pac_ctx* ctx, uint64_t capacity);
+
+/* Test hook: the number of polls after which a workgroup of the prefix scan stops waiting for an
+ * earlier tile (default 2^22; 0 = give up on the first value that is not there yet).  A workgroup that
+ * gives up still finishes normally and raises PAC_DEV_SCAN_STALLED.  Exists so that a test can see
+ * that flag without a kernel that hangs. */
+pac_status pac_debug_set_scan_spin_limit(pac_ctx* ctx, uint32_t polls);
 
 #ifdef __cplusplus
 }

@@ -159,9 +159,9 @@ def mask_diff(a: np.ndarray, b: np.ndarray, n: int) -> int:
 
 
 class MaskTracker:
-    """The Mask Tracker's bookkeeping (Sec. III-B; Alg. 1 "update sparse mask using Mask Tracker"):
+    """The Mask Tracker's bookkeeping (Sec. III-B; Alg. 1, mask-update step and stability test):
     keep the previous iteration's mask, compare, and call the pattern stable once it has stayed
-    unchanged for `patience` consecutive comparisons.  The paper says "multiple iterations" without
+    unchanged for `patience` consecutive comparisons.  The paper asks for several unchanged iterations without
     a number: `patience` is the caller's.  The first mask ever seen, and a mask of another length,
     count as a change."""
 

@@ -225,7 +225,7 @@ void orc_f32_to_bf16(const float* in, uint16_t* out, uint64_t n) {
 // ---- around the hot path: Mask Tracker and the weight update -------------------------------
 
 // Mask of the non-zero elements of a flat tensor: the (Weight != 0) of Eq. 2, which is also how
-// the Mask Tracker (Sec. III-B, "Mask Tracker mechanism") reads the sparsity pattern off a
+// the Mask Tracker (Sec. III-B, Mask Tracker paragraph) reads the sparsity pattern off a
 // flattened bucket without names or shapes.  "!= 0" is the IEEE comparison: -0 is zero, NaN
 // and denormals are non-zero.  bf16 values are compared after exact widening.
 // Writes the bitmask (bits >= n zero) and the exclusive prefix; returns the number of set bits.
@@ -280,7 +280,7 @@ uint64_t orc_decompress_update(const void* compact, int dtype, uint64_t nnz, con
     return next;
 }
 
-// ---- ternary payload (Sec. III-D "Pruning with Gradient Quantization") ---------------------
+// ---- ternary payload (Sec. III-D) ---------------------
 // ternarize(.) of Sec. III-D is the TernGrad quantiser the section names: with a scale s >= max|g|,
 // every element becomes s * sign(g) * b with b ~ Bernoulli(|g| / s), so that E[s * t] = g (Eq. 3 is
 // that expectation).  The paper fixes neither the random source nor the layout; here:

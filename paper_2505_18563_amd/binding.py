@@ -15,6 +15,15 @@ from . import build as _build
 PAC_F32 = 0
 PAC_BF16 = 1
 PAC_MAX_WORKERS = 64
+PAC_TABLE_SLOTS = 4
+
+# bits of the device status word (pac_device_status)
+PAC_DEV_SCAN_STALLED = 0x01
+PAC_DEV_COUNT_MISMATCH = 0x02
+PAC_DEV_META_MISMATCH = 0x04
+PAC_DEV_RETRY_TAKEN = 0x100
+PAC_DEV_SLOW_PATH = 0x200
+PAC_DEV_ERROR_MASK = 0xFF
 
 _STATUS_NAMES = {0: "PAC_OK", -1: "PAC_ERR_ARG", -2: "PAC_ERR_ALIGN", -3: "PAC_ERR_RANGE",
                  -4: "PAC_ERR_COUNT", -5: "PAC_ERR_HIP", -6: "PAC_ERR_NOMEM"}
@@ -62,6 +71,10 @@ def load_library() -> ctypes.CDLL:
     lib.pac_decompress.argtypes = [vp, vp, i32, u64, vp, vp, vp, u64, vp]
     lib.pac_debug_set_candidate_capacity.restype = i32
     lib.pac_debug_set_candidate_capacity.argtypes = [vp, u64]
+    lib.pac_debug_set_scan_spin_limit.restype = i32
+    lib.pac_debug_set_scan_spin_limit.argtypes = [vp, u32]
+    lib.pac_device_status.restype = i32
+    lib.pac_device_status.argtypes = [vp, vp, ctypes.POINTER(u32), ctypes.c_int, vp]
     lib.pac_mask_from_nonzero.restype = i32
     lib.pac_mask_from_nonzero.argtypes = [vp, vp, i32, u64, vp, vp, vp, vp]
     lib.pac_mask_equal.restype = i32
@@ -140,6 +153,23 @@ def pac_destroy(ctx) -> None:
 
 def pac_debug_set_candidate_capacity(ctx, capacity: int) -> None:
     _check(ctx, load_library().pac_debug_set_candidate_capacity(ctx, int(capacity)))
+
+
+def pac_debug_set_scan_spin_limit(ctx, polls: int) -> None:
+    _check(ctx, load_library().pac_debug_set_scan_spin_limit(ctx, int(polls)))
+
+
+def pac_device_status(ctx, flags_out: Optional[torch.Tensor] = None, to_host: bool = True, clear: bool = False,
+                      stream=None) -> Optional[int]:
+    """flags_out: device int32 [1] that receives the status word in stream order.  With to_host the call
+    waits for the stream and returns the word; otherwise it returns None."""
+    if flags_out is not None and (flags_out.dtype != torch.int32 or flags_out.numel() < 1):
+        raise TypeError("flags_out must be an int32 tensor")
+    host = ctypes.c_uint32(0)
+    st = load_library().pac_device_status(ctx, _dev_ptr(flags_out), ctypes.byref(host) if to_host else None,
+                                          1 if clear else 0, _stream_ptr(stream))
+    _check(ctx, st)
+    return int(host.value) if to_host else None
 
 
 def pac_build_mask(ctx, weights: torch.Tensor, seg_offsets: Sequence[int], sparsity: Sequence[float],
@@ -341,6 +371,10 @@ class PacContext:
 
     def _dev(self):
         return torch.device("cuda", self.device)
+
+    def device_status(self, clear: bool = False, stream=None) -> int:
+        """The context's device status word (PAC_DEV_* bits); waits for the stream."""
+        return pac_device_status(self.handle, None, True, clear, stream)
 
     def build_mask(self, weights: torch.Tensor, seg_offsets=None, sparsity=0.0, mask=None, prefix=None,
                    stream=None) -> Tuple[torch.Tensor, torch.Tensor, int]:

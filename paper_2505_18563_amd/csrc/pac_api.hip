@@ -12,11 +12,27 @@
 
 namespace {
 
-constexpr int kRing = 4;               // pinned staging slots for the segment table
+constexpr int kTableSlots = (int)PAC_TABLE_SLOTS;   // scope tables kept resident on the device
 constexpr uint32_t kMaxSegments = 65535;   // scopes index a grid dimension
-constexpr uint64_t kScanTileWords = 2048;  // not larger than the smallest tile the scan kernel uses
+
+static_assert(pac::kDevScanStalled == PAC_DEV_SCAN_STALLED && pac::kDevCountMismatch == PAC_DEV_COUNT_MISMATCH &&
+              pac::kDevMetaMismatch == PAC_DEV_META_MISMATCH && pac::kDevRetryTaken == PAC_DEV_RETRY_TAKEN &&
+              pac::kDevSlowPath == PAC_DEV_SLOW_PATH, "status bits of the kernels and of the header");
 
 thread_local char g_create_error[256] = "";
+
+// One scope table resident on the device, with what the kernels derive from it.
+struct TableSlot {
+    pac::SegDesc* d_seg = nullptr;        // [max_segments]
+    uint32_t* d_tile_scope = nullptr;     // [tiles]
+    pac::SegDesc* h_stage = nullptr;      // pinned: the upload reads it asynchronously
+    hipEvent_t uploaded = nullptr;        // recorded behind the upload
+    bool upload_recorded = false;
+    bool valid = false;
+    bool captured = false;                // baked into a graph: never replaced
+    uint64_t last_use = 0;
+    std::vector<pac::SegDesc> table;      // what d_seg holds
+};
 
 }  // namespace
 
@@ -25,14 +41,11 @@ struct pac_ctx {
     int num_cu = 0;
     uint64_t max_elems = 0;
     uint32_t max_segments = 0;
-    pac::MaskScratch scratch{};
-    // segment table staging
-    pac::SegDesc* h_ring[kRing] = {nullptr, nullptr, nullptr, nullptr};
-    hipEvent_t ring_event[kRing] = {nullptr, nullptr, nullptr, nullptr};
-    bool ring_used[kRing] = {false, false, false, false};
-    int ring_next = 0;
-    std::vector<pac::SegDesc> last_table;   // what the device table currently holds
-    bool table_valid = false;
+    pac::MaskScratch scratch{};           // seg / tile_scope are set per call from a table slot
+    TableSlot slots[kTableSlots];
+    uint64_t use_clock = 0;
+    uint32_t* d_status_copy = nullptr;    // device word pac_device_status copies through
+    uint32_t* h_status = nullptr;         // pinned
     char err[256] = "";
 };
 
@@ -56,6 +69,18 @@ pac_status fail(pac_ctx* ctx, pac_status code, const char* fmt, ...) {
     va_end(ap);
     return code;
 }
+
+}  // namespace
+
+int32_t pac::thread_fail(int32_t code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_create_error, sizeof g_create_error, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+namespace {
 
 // Makes the context's device current for the duration of a call and restores the caller's.
 struct DeviceGuard {
@@ -90,23 +115,26 @@ uint32_t sample_stride(uint64_t len) {
 
 void free_scratch(pac_ctx* ctx) {
     pac::MaskScratch& s = ctx->scratch;
-    (void)hipFree(s.seg);
+    (void)hipFree(s.status);
+    (void)hipFree(ctx->d_status_copy);
+    if (ctx->h_status) (void)hipHostFree(ctx->h_status);
     (void)hipFree(s.state);
     (void)hipFree(s.hist0);
     (void)hipFree(s.hist1);
     (void)hipFree(s.kept_above);
     (void)hipFree(s.glob);
     (void)hipFree(s.rec);
-    (void)hipFree(s.tile_scope);
     (void)hipFree(s.match);
     (void)hipFree(s.match_count);
     (void)hipFree(s.tile_state);
     if (s.side_stream) (void)hipStreamDestroy(s.side_stream);
     if (s.fork_event) (void)hipEventDestroy(s.fork_event);
     if (s.join_event) (void)hipEventDestroy(s.join_event);
-    for (int i = 0; i < kRing; ++i) {
-        if (ctx->h_ring[i]) (void)hipHostFree(ctx->h_ring[i]);
-        if (ctx->ring_event[i]) (void)hipEventDestroy(ctx->ring_event[i]);
+    for (TableSlot& t : ctx->slots) {
+        (void)hipFree(t.d_seg);
+        (void)hipFree(t.d_tile_scope);
+        if (t.h_stage) (void)hipHostFree(t.h_stage);
+        if (t.uploaded) (void)hipEventDestroy(t.uploaded);
     }
 }
 
@@ -163,8 +191,6 @@ pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_
     pac::MaskScratch& s = ctx->scratch;
     s.cand_cap = ~0ull;   // every tile record may use all of its slots
     const uint64_t emit_tiles = (max_elems + pac::kEmitTileElems - 1) / pac::kEmitTileElems;
-    const uint64_t words = pac_mask_words(max_elems);
-    const uint64_t scan_tiles = (words + kScanTileWords - 1) / kScanTileWords;
     const size_t hist0_bytes = (size_t)max_segments * pac::kDigit0Bins * sizeof(uint32_t);
     const size_t hist1_bytes = (size_t)max_segments * pac::kDigit1Bins * sizeof(uint32_t);
     bool ok = true;
@@ -177,23 +203,33 @@ pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_
             code = fail(nullptr, PAC_ERR_NOMEM, "pac_create: hipMalloc(%zu): %s", bytes, hipGetErrorString(r));
         }
     };
-    alloc((void**)&s.seg, (size_t)max_segments * sizeof(pac::SegDesc));
+    alloc((void**)&s.status, sizeof(uint32_t));
+    alloc((void**)&ctx->d_status_copy, sizeof(uint32_t));
     alloc((void**)&s.state, (size_t)max_segments * sizeof(pac::SegState));
     alloc((void**)&s.hist0, hist0_bytes);
     alloc((void**)&s.hist1, hist1_bytes);
     alloc((void**)&s.kept_above, (size_t)max_segments * sizeof(uint32_t));
     alloc((void**)&s.glob, sizeof(pac::Globals));
     alloc((void**)&s.rec, (size_t)emit_tiles * pac::kRecSlots * sizeof(unsigned long long));
-    alloc((void**)&s.tile_scope, (size_t)emit_tiles * sizeof(uint32_t));
     alloc((void**)&s.match, (size_t)pac::kMatchSlots * sizeof(unsigned long long));
     alloc((void**)&s.match_count, (size_t)pac::kMatchBlocks * sizeof(uint32_t));
-    alloc((void**)&s.tile_state, (size_t)(scan_tiles + 1) * sizeof(unsigned long long));
-    for (int i = 0; ok && i < kRing; ++i) {
-        hipError_t r = hipHostMalloc((void**)&ctx->h_ring[i], (size_t)max_segments * sizeof(pac::SegDesc), hipHostMallocDefault);
-        if (r == hipSuccess) r = hipEventCreateWithFlags(&ctx->ring_event[i], hipEventDisableTiming);
+    alloc((void**)&s.tile_state, (size_t)(pac::kScanMaxTiles + 1) * sizeof(unsigned long long));
+    for (TableSlot& t : ctx->slots) {
+        alloc((void**)&t.d_seg, (size_t)max_segments * sizeof(pac::SegDesc));
+        alloc((void**)&t.d_tile_scope, (size_t)emit_tiles * sizeof(uint32_t));
+        if (!ok) break;
+        hipError_t r = hipHostMalloc((void**)&t.h_stage, (size_t)max_segments * sizeof(pac::SegDesc), hipHostMallocDefault);
+        if (r == hipSuccess) r = hipEventCreateWithFlags(&t.uploaded, hipEventDisableTiming);
         if (r != hipSuccess) {
             ok = false;
             code = fail(nullptr, PAC_ERR_NOMEM, "pac_create: pinned staging: %s", hipGetErrorString(r));
+        }
+    }
+    if (ok) {
+        hipError_t r = hipHostMalloc((void**)&ctx->h_status, sizeof(uint32_t), hipHostMallocDefault);
+        if (r != hipSuccess) {
+            ok = false;
+            code = fail(nullptr, PAC_ERR_NOMEM, "pac_create: pinned status word: %s", hipGetErrorString(r));
         }
     }
     if (ok) {
@@ -212,12 +248,15 @@ pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_
             ok = false;
             code = fail(nullptr, PAC_ERR_HIP, "pac_create: kernel attributes: %s", hipGetErrorString(r));
         }
+        s.hist_blocks = pac::mask_hist_blocks(ctx->num_cu);
+        s.scan_spin_limit = 1u << 22;
     }
     if (ok) {
         // The histograms are all-zero between calls: the kernels that read them clear them.
         hipError_t r = hipMemset(s.hist0, 0, hist0_bytes);
         if (r == hipSuccess) r = hipMemset(s.hist1, 0, hist1_bytes);
         if (r == hipSuccess) r = hipMemset(s.glob, 0, sizeof(pac::Globals));
+        if (r == hipSuccess) r = hipMemset(s.status, 0, sizeof(uint32_t));
         if (r == hipSuccess) r = hipMemset(s.state, 0, (size_t)max_segments * sizeof(pac::SegState));
         if (r == hipSuccess) r = hipDeviceSynchronize();
         if (r != hipSuccess) {
@@ -246,6 +285,32 @@ pac_status pac_destroy(pac_ctx* ctx) {
 pac_status pac_debug_set_candidate_capacity(pac_ctx* ctx, uint64_t capacity) {
     if (!ctx) return PAC_ERR_ARG;
     ctx->scratch.cand_cap = capacity;
+    return PAC_OK;
+}
+
+pac_status pac_debug_set_scan_spin_limit(pac_ctx* ctx, uint32_t polls) {
+    if (!ctx) return PAC_ERR_ARG;
+    ctx->scratch.scan_spin_limit = polls;
+    return PAC_OK;
+}
+
+pac_status pac_device_status(pac_ctx* ctx, uint32_t* d_flags_out, uint32_t* h_flags_out, int clear, void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    if (!d_flags_out && !h_flags_out && !clear) return PAC_OK;
+    if (!is_aligned(d_flags_out, 4)) return fail(ctx, PAC_ERR_ALIGN, "pac_device_status: d_flags_out not 4-byte aligned");
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess)
+        return fail(ctx, PAC_ERR_HIP, "pac_device_status: hipSetDevice: %s", hipGetErrorString(guard.status));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // One read serves both destinations, so that a clearing read loses nothing.
+    uint32_t* d_dst = d_flags_out ? d_flags_out : (h_flags_out ? ctx->d_status_copy : nullptr);
+    hipError_t r = pac::launch_status_read(ctx->scratch.status, d_dst, clear != 0, stream);
+    if (r == hipSuccess && h_flags_out) {
+        r = hipMemcpyAsync(ctx->h_status, d_dst, sizeof(uint32_t), hipMemcpyDeviceToHost, stream);
+        if (r == hipSuccess) r = hipStreamSynchronize(stream);
+        if (r == hipSuccess) *h_flags_out = *ctx->h_status;
+    }
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_device_status: %s", hipGetErrorString(r));
     return PAC_OK;
 }
 
@@ -300,32 +365,63 @@ pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n, cons
         return fail(ctx, PAC_ERR_HIP, "pac_build_mask: hipSetDevice: %s", hipGetErrorString(guard.status));
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-    // Upload the table only when it differs from what the device holds (steady state: never).
-    const bool same = ctx->table_valid && ctx->last_table.size() == table.size() &&
-                      std::memcmp(ctx->last_table.data(), table.data(), table.size() * sizeof(pac::SegDesc)) == 0;
-    if (!same) {
-        const int slot = ctx->ring_next;
-        ctx->ring_next = (slot + 1) % kRing;
-        if (ctx->ring_used[slot]) {
-            hipError_t r = hipEventSynchronize(ctx->ring_event[slot]);   // the copy that last read this slot
-            if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_build_mask: hipEventSynchronize: %s", hipGetErrorString(r));
-        }
-        std::memcpy(ctx->h_ring[slot], table.data(), table.size() * sizeof(pac::SegDesc));
-        hipError_t r = hipMemcpyAsync(ctx->scratch.seg, ctx->h_ring[slot], table.size() * sizeof(pac::SegDesc),
-                                      hipMemcpyHostToDevice, stream);
-        if (r == hipSuccess) r = hipEventRecord(ctx->ring_event[slot], stream);
-        if (r != hipSuccess) {
-            ctx->table_valid = false;
-            return fail(ctx, PAC_ERR_HIP, "pac_build_mask: segment table upload: %s", hipGetErrorString(r));
-        }
-        ctx->ring_used[slot] = true;
-        ctx->last_table.swap(table);
-        ctx->table_valid = true;
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capture) != hipSuccess) {
+        (void)hipGetLastError();
+        capture = hipStreamCaptureStatusNone;
     }
+    const bool capturing = capture != hipStreamCaptureStatusNone;
 
-    hipError_t r = pac::launch_build_mask(ctx->scratch, d_weights, (uint32_t)n, nseg, sampled, any_sampled, max_tiny, max_small,
-                                          !same, reinterpret_cast<unsigned long long*>(d_mask), d_prefix, ctx->num_cu, stream);
-    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_build_mask: launch: %s", hipGetErrorString(r));
+    // The table among the resident ones (steady state, also of a cyclic sparsity schedule): nothing to upload.
+    TableSlot* slot = nullptr;
+    for (TableSlot& t : ctx->slots) {
+        if (t.valid && t.table.size() == table.size() &&
+            std::memcmp(t.table.data(), table.data(), table.size() * sizeof(pac::SegDesc)) == 0) {
+            slot = &t;
+            break;
+        }
+    }
+    const bool fresh = slot == nullptr;
+    if (fresh) {
+        if (capturing)
+            return fail(ctx, PAC_ERR_ARG, "pac_build_mask: this scope table is not resident on the device and the stream "
+                                          "is being captured; run the call once outside the capture first");
+        // Replace a slot that holds nothing, else the least recently used one that no graph refers to.
+        for (TableSlot& t : ctx->slots) {
+            if (t.captured) continue;
+            if (!slot || (!t.valid && slot->valid) || (t.valid == slot->valid && t.last_use < slot->last_use)) slot = &t;
+        }
+        if (!slot)
+            return fail(ctx, PAC_ERR_RANGE, "pac_build_mask: all %d scope-table slots are held by captured graphs", kTableSlots);
+        if (slot->upload_recorded) {
+            // The pinned staging block may be rewritten only after the upload that last read it has run:
+            // true long ago unless more than kTableSlots tables alternate faster than the device follows.
+            hipError_t q = hipEventQuery(slot->uploaded);
+            if (q == hipErrorNotReady) q = hipEventSynchronize(slot->uploaded);
+            if (q != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_build_mask: waiting for an earlier table upload: %s", hipGetErrorString(q));
+        }
+        slot->valid = false;
+        std::memcpy(slot->h_stage, table.data(), table.size() * sizeof(pac::SegDesc));
+        hipError_t r = hipMemcpyAsync(slot->d_seg, slot->h_stage, table.size() * sizeof(pac::SegDesc),
+                                      hipMemcpyHostToDevice, stream);
+        if (r == hipSuccess) r = hipEventRecord(slot->uploaded, stream);
+        if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_build_mask: scope table upload: %s", hipGetErrorString(r));
+        slot->upload_recorded = true;
+        slot->table.swap(table);
+        slot->valid = true;
+    }
+    slot->last_use = ++ctx->use_clock;
+    if (capturing) slot->captured = true;
+
+    pac::MaskScratch call = ctx->scratch;
+    call.seg = slot->d_seg;
+    call.tile_scope = slot->d_tile_scope;
+    hipError_t r = pac::launch_build_mask(call, d_weights, (uint32_t)n, nseg, sampled, any_sampled, max_tiny, max_small,
+                                          fresh, reinterpret_cast<unsigned long long*>(d_mask), d_prefix, total, stream);
+    if (r != hipSuccess) {
+        if (fresh) slot->valid = false;   // its tile_scope may not have been filled
+        return fail(ctx, PAC_ERR_HIP, "pac_build_mask: launch: %s", hipGetErrorString(r));
+    }
     return PAC_OK;
 }
 
@@ -351,7 +447,8 @@ pac_status pac_compress(pac_ctx* ctx, const void* d_grad, pac_dtype dtype, uint6
     DeviceGuard guard(ctx->device);
     if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_compress: hipSetDevice: %s", hipGetErrorString(guard.status));
     hipError_t r = pac::launch_compress(d_grad, (int)dtype, (uint32_t)n, reinterpret_cast<const unsigned long long*>(d_mask),
-                                        d_prefix, d_compact, (uint32_t)nnz, static_cast<hipStream_t>(hip_stream));
+                                        d_prefix, d_compact, (uint32_t)nnz, ctx->scratch.status,
+                                        static_cast<hipStream_t>(hip_stream));
     if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_compress: launch: %s", hipGetErrorString(r));
     return PAC_OK;
 }
@@ -364,7 +461,8 @@ pac_status pac_decompress(pac_ctx* ctx, const void* d_compact, pac_dtype dtype, 
     DeviceGuard guard(ctx->device);
     if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_decompress: hipSetDevice: %s", hipGetErrorString(guard.status));
     hipError_t r = pac::launch_decompress(d_compact, (int)dtype, (uint32_t)nnz, reinterpret_cast<const unsigned long long*>(d_mask),
-                                          d_prefix, d_dense_out, (uint32_t)n, static_cast<hipStream_t>(hip_stream));
+                                          d_prefix, d_dense_out, (uint32_t)n, ctx->scratch.status,
+                                          static_cast<hipStream_t>(hip_stream));
     if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "pac_decompress: launch: %s", hipGetErrorString(r));
     return PAC_OK;
 }
@@ -419,7 +517,7 @@ pac_status pac_mask_from_nonzero(pac_ctx* ctx, const void* d_values, pac_dtype d
         r = pac::launch_nonzero_mask(d_values, (int)dtype, (uint32_t)n, reinterpret_cast<unsigned long long*>(d_mask), stream);
         if (r == hipSuccess)
             r = pac::launch_prefix_scan(ctx->scratch, reinterpret_cast<const unsigned long long*>(d_mask),
-                                        (uint32_t)pac_mask_words(n), d_prefix, total, stream);
+                                        (uint32_t)pac_mask_words(n), d_prefix, total, /*reset_status=*/false, stream);
     }
     if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: launch: %s", who, hipGetErrorString(r));
     return PAC_OK;
@@ -525,7 +623,8 @@ pac_status pac_decompress_update(pac_ctx* ctx, const void* d_reduced, pac_dtype 
     if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: hipSetDevice: %s", who, hipGetErrorString(guard.status));
     hipError_t r = pac::launch_decompress_update(d_reduced, (int)dtype, (uint32_t)nnz,
                                                  reinterpret_cast<const unsigned long long*>(d_mask), d_prefix, alpha,
-                                                 d_weights, (uint32_t)n, static_cast<hipStream_t>(hip_stream));
+                                                 d_weights, (uint32_t)n, ctx->scratch.status,
+                                                 static_cast<hipStream_t>(hip_stream));
     if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: launch: %s", who, hipGetErrorString(r));
     return PAC_OK;
 }

@@ -75,19 +75,30 @@ struct Globals {
     uint32_t retry;                      // a sampled bracket missed the k-th element: redo with full counts
     uint32_t match_overflow;             // a workgroup of compact2 ran out of match slots
     uint32_t scan_ticket;                // next tile of the prefix scan
-    uint32_t scan_stalled;               // set if a scan workgroup gave up waiting (never expected)
-    uint32_t pad[4];
+    uint32_t pad[5];
 };
 
+// Bits of the context's device status word; the values are those of the PAC_DEV_* enumerators of the
+// public header (checked where both are visible).
+constexpr uint32_t kDevScanStalled = 0x01u;
+constexpr uint32_t kDevCountMismatch = 0x02u;
+constexpr uint32_t kDevMetaMismatch = 0x04u;
+constexpr uint32_t kDevRetryTaken = 0x100u;
+constexpr uint32_t kDevSlowPath = 0x200u;
+constexpr unsigned long long kNoExpectedTotal = ~0ull;   // "do not check the scan's total"
+
 struct MaskScratch {
-    SegDesc* seg;                  // [max_segments]
+    uint32_t* status;              // the context's device status word (sticky PAC_DEV_* bits)
+    uint32_t scan_spin_limit;      // polls after which a scan workgroup gives up waiting (a test hook lowers it)
+    uint32_t hist_blocks;          // workgroups of the first histogram pass that fit on the device at once
+    SegDesc* seg;                  // [max_segments] scope table of the current call (one of the context's resident tables)
     SegState* state;               // [max_segments]
     uint32_t* hist0;               // [max_segments * kDigit0Bins], all zero between calls
     uint32_t* hist1;               // [max_segments * kDigit1Bins], all zero between calls
     uint32_t* kept_above;          // [max_segments] elements with key >= hi (counted for sampled scopes)
     Globals* glob;
     unsigned long long* rec;       // [tiles * kRecSlots] tile records
-    uint32_t* tile_scope;          // [tiles] scope of each tile's first element (for the current table)
+    uint32_t* tile_scope;          // [tiles] scope of each tile's first element (belongs to the table in `seg`)
     unsigned long long* match;     // [kMatchSlots] undecided elements whose digit 1 is their scope's bin1 as
                                    // well, kMatchSlotsPerBlock slots per workgroup of compact2
     uint32_t* match_count;         // [kMatchBlocks] slots used by each workgroup
@@ -107,28 +118,47 @@ struct MaskScratch {
 // length in the table (0 = none).  `table_changed`: the scope table on the device is not the one of
 // the previous call.
 constexpr uint32_t kTinyScope = 4096;
+// `fresh_table`: s.tile_scope has not been filled for the table in s.seg yet.  `expect_total`: the sum of
+// the scopes' keep counts (the scan raises kDevCountMismatch if the mask holds another number of bits).
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
                              uint64_t sampled_elems, bool any_sampled, uint32_t max_tiny, uint32_t max_small,
-                             bool table_changed, unsigned long long* d_mask, uint32_t* d_prefix, int num_cu,
-                             hipStream_t stream);
+                             bool fresh_table, unsigned long long* d_mask, uint32_t* d_prefix,
+                             unsigned long long expect_total, hipStream_t stream);
 // Raises the small-scope kernel's LDS limit; once per device, before the first launch.
 hipError_t prepare_mask_kernels();
+// Workgroups of the first histogram pass that fit on a device with `num_cu` compute units at once.
+uint32_t mask_hist_blocks(int num_cu);
 
-// prefix[j] = set bits in words < j of any mask of at most the context's max_elems bits;
-// *d_total_out (device, may be null) receives the number of set bits.  Uses the context's scan scratch.
+// prefix[j] = set bits in words < j of any mask of at most 2^32 - 1 bits; *d_total_out (device, may be
+// null) receives the number of set bits.  Uses s.tile_state (at least kScanMaxTiles + 1 words),
+// s.glob, s.status and s.scan_spin_limit only.
+constexpr uint32_t kScanMaxTiles = 2048;
+// `reset_status`: the kernel that clears the scan state also zeroes *s.status (for scratch that is
+// shared by unrelated calls; a context's status word is sticky and is left alone).
 hipError_t launch_prefix_scan(const MaskScratch& s, const unsigned long long* d_mask, uint32_t words,
-                              uint32_t* d_prefix, unsigned long long* d_total_out, hipStream_t stream);
+                              uint32_t* d_prefix, unsigned long long* d_total_out, bool reset_status,
+                              hipStream_t stream);
 
+// Records a formatted error text where pac_last_error(NULL) finds it (calls without a context) and
+// returns `code`.
+int32_t thread_fail(int32_t code, const char* fmt, ...);
+
+// d_status: the device status word that receives kDevMetaMismatch / kDevCountMismatch.
 hipError_t launch_compress(const void* d_grad, int dtype, uint32_t n, const unsigned long long* d_mask,
-                           const uint32_t* d_prefix, void* d_compact, uint32_t nnz, hipStream_t stream);
+                           const uint32_t* d_prefix, void* d_compact, uint32_t nnz, uint32_t* d_status,
+                           hipStream_t stream);
 
 hipError_t launch_decompress(const void* d_compact, int dtype, uint32_t nnz, const unsigned long long* d_mask,
-                             const uint32_t* d_prefix, void* d_dense, uint32_t n, hipStream_t stream);
+                             const uint32_t* d_prefix, void* d_dense, uint32_t n, uint32_t* d_status,
+                             hipStream_t stream);
 
 // x <- x - alpha * g on kept weights (g = the next value of the summed compact buffer), +0 on pruned ones.
 hipError_t launch_decompress_update(const void* d_compact, int dtype, uint32_t nnz, const unsigned long long* d_mask,
                                     const uint32_t* d_prefix, float alpha, float* d_weights, uint32_t n,
-                                    hipStream_t stream);
+                                    uint32_t* d_status, hipStream_t stream);
+
+// Copies the status word to d_out (may be null) and, with clear, resets it; one thread.
+hipError_t launch_status_read(uint32_t* d_status, uint32_t* d_out, bool clear, hipStream_t stream);
 
 // Mask Tracker kernels (pac_track.hip).
 hipError_t launch_nonzero_mask(const void* d_values, int dtype, uint32_t n, unsigned long long* d_mask,

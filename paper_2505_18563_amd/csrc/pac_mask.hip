@@ -430,7 +430,8 @@ __global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(const SegDesc
                                                                    SegState* __restrict__ state,
                                                                    uint32_t* __restrict__ hist1,
                                                                    const uint32_t* __restrict__ kept_above,
-                                                                   Globals* glob, uint32_t pass) {
+                                                                   Globals* glob, uint32_t* __restrict__ status,
+                                                                   uint32_t pass) {
     __shared__ uint32_t wave_sums[kDigit1Bins / 16 / 64];
     __shared__ uint32_t sh_rank;
     if (pass != 0 && !glob->retry) return;
@@ -462,10 +463,14 @@ __global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(const SegDesc
     if (mine) {
         st->krem0 = rank; st->bin1 = bin; st->cnt1 = cnt; st->krem1 = krem;
         st->heavy = cnt > kFinalList ? 1u : 0u;
+        if (cnt > kFinalList) atomicOr(status, kDevSlowPath);
         sh_rank = 1;
     }
     __syncthreads();
-    if (threadIdx.x == 0 && active && sh_rank == 0) glob->retry = 1;   // the bracket missed the k-th element
+    if (threadIdx.x == 0 && active && sh_rank == 0) {   // the bracket missed the k-th element
+        glob->retry = 1;
+        atomicOr(status, kDevRetryTaken);
+    }
 }
 
 // -------------------------------------------------------------------------------------- emit
@@ -850,7 +855,8 @@ __global__ __launch_bounds__(kListBlock) void compact2_kernel(const float* __res
                                                               const SegState* __restrict__ state, Globals* glob,
                                                               const uint32_t* __restrict__ tile_scope,
                                                               const u64* __restrict__ rec, u64* __restrict__ match,
-                                                              uint32_t* __restrict__ match_count) {
+                                                              uint32_t* __restrict__ match_count,
+                                                              uint32_t* __restrict__ status) {
     __shared__ u64 found[kMatchSlotsPerBlock];
     __shared__ WalkShared ws[kListBlock / 64];
     __shared__ uint32_t nfound;
@@ -872,7 +878,10 @@ __global__ __launch_bounds__(kListBlock) void compact2_kernel(const float* __res
     }
     __syncthreads();
     const uint32_t total = nfound;
-    if (total > kMatchSlotsPerBlock && threadIdx.x == 0) glob->match_overflow = 1;   // `final` uses the weights
+    if (total > kMatchSlotsPerBlock && threadIdx.x == 0) {   // `final` uses the weights
+        glob->match_overflow = 1;
+        atomicOr(status, kDevSlowPath);
+    }
     const uint32_t kept = min(total, kMatchSlotsPerBlock);
     if (threadIdx.x < kept) match[(size_t)blockIdx.x * kMatchSlotsPerBlock + threadIdx.x] = found[threadIdx.x];
     if (threadIdx.x == 0) match_count[blockIdx.x] = kept;
@@ -1132,7 +1141,9 @@ __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restri
 // over its predecessors' published values until it meets one that already holds an inclusive
 // prefix.  Status and value share one 64-bit word, read and written with device-scope atomics, so
 // no other data needs ordering across the XCDs' L2 caches.  The wait for a predecessor is bounded:
-// a workgroup that gives up raises `scan_stalled` and finishes (with wrong offsets) rather than spin.
+// a workgroup that gives up raises kDevScanStalled in the context's status word and finishes (with
+// wrong offsets) rather than spin; the caller reads the word with pac_device_status.  The last tile
+// compares the total with the count the host expects (kDevCountMismatch).
 // The tile size follows the size of the mask (scan_iters_for): a tile per workgroup must be small
 // enough for the tiles to fill the chip, and large enough that the look-back chain stays short.
 constexpr int kScanBlock = 1024;
@@ -1140,7 +1151,6 @@ constexpr int kScanWaves = kScanBlock / 64;
 constexpr uint32_t scan_tile_words(uint32_t iters) { return kScanWaves * 64u * 2u * iters; }   // iters 16-byte loads per lane
 constexpr u64 kTileAggregate = 1ull << 32;   // value = bits in this tile
 constexpr u64 kTileInclusive = 2ull << 32;   // value = bits in this tile and all before it
-constexpr uint32_t kScanSpinLimit = 1u << 22;
 
 __device__ __forceinline__ u64 tile_load(const u64* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1153,7 +1163,8 @@ template <uint32_t kScanIters>
 __global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __restrict__ mask, uint32_t words,
                                                                    u64* __restrict__ tile_state, Globals* glob,
                                                                    uint32_t* __restrict__ prefix,
-                                                                   u64* __restrict__ total_out) {
+                                                                   u64* __restrict__ total_out, u64 expect_total,
+                                                                   uint32_t* __restrict__ status, uint32_t spin_limit) {
     __shared__ uint32_t ex_lds[kScanIters][kScanBlock];
     __shared__ uint32_t wave_totals[kScanWaves];
     __shared__ uint32_t sh_tile, sh_base;
@@ -1214,7 +1225,7 @@ __global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __
                 uint32_t spins = 0;
                 while (__any((st >> 32) == 0)) {
                     if ((st >> 32) == 0) st = tile_load(slot);
-                    if (++spins > kScanSpinLimit) { stalled = true; break; }
+                    if (++spins > spin_limit) { stalled = true; break; }
                     __builtin_amdgcn_s_sleep(1);
                 }
                 if (stalled) break;
@@ -1228,7 +1239,7 @@ __global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __
                 window -= 64;
             }
             if (lane == 0) {
-                if (stalled) glob->scan_stalled = 1;
+                if (stalled) atomicOr(status, kDevScanStalled);
                 tile_store(&tile_state[tile], kTileInclusive | (u64)(before + tile_total));
                 sh_base = before;
             }
@@ -1237,7 +1248,11 @@ __global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __
     __syncthreads();
     const uint32_t base = sh_base + wave_off;
     // the last tile knows the number of set bits of the whole mask
-    if (total_out != nullptr && tile == gridDim.x - 1 && threadIdx.x == 0) *total_out = (u64)sh_base + tile_total;
+    if (tile == gridDim.x - 1 && threadIdx.x == 0) {
+        const u64 total = (u64)sh_base + tile_total;
+        if (total_out != nullptr) *total_out = total;
+        if (expect_total != kNoExpectedTotal && total != expect_total) atomicOr(status, kDevCountMismatch);
+    }
 #pragma unroll
     for (uint32_t it = 0; it < kScanIters; ++it) {
         const u64 w0 = wave_first + it * 128u + lane * 2u;
@@ -1251,10 +1266,13 @@ __global__ __launch_bounds__(kScanBlock) void scan_lookback_kernel(const u64* __
 }
 
 // Clears the scan's tile states and ticket for a scan that does not follow a mask build.
-__global__ void scan_reset_kernel(u64* __restrict__ tile_state, uint32_t tiles, Globals* glob) {
+__global__ void scan_reset_kernel(u64* __restrict__ tile_state, uint32_t tiles, Globals* glob, uint32_t* clear_status) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i <= tiles) tile_state[i] = 0;
-    if (i == 0) { glob->scan_ticket = 0; glob->scan_stalled = 0; }
+    if (i == 0) {
+        glob->scan_ticket = 0;
+        if (clear_status != nullptr) *clear_status = 0;
+    }
 }
 
 inline uint32_t div_up_u64(u64 a, u64 b) { return (uint32_t)((a + b - 1) / b); }
@@ -1264,22 +1282,27 @@ inline uint32_t div_up_u64(u64 a, u64 b) { return (uint32_t)((a + b - 1) / b); }
 inline uint32_t scan_iters_for(uint32_t words) { return words <= (1u << 19) ? 2u : words <= (1u << 22) ? 4u : 16u; }
 inline uint32_t scan_tiles_for(uint32_t words) { return div_up_u64(words, scan_tile_words(scan_iters_for(words))); }
 
-inline void launch_scan(const u64* d_mask, uint32_t words, u64* tile_state, Globals* glob, uint32_t* d_prefix,
-                        u64* d_total_out, hipStream_t stream) {
+inline void launch_scan(const MaskScratch& s, const u64* d_mask, uint32_t words, uint32_t* d_prefix,
+                        u64* d_total_out, u64 expect_total, hipStream_t stream) {
     const uint32_t tiles = scan_tiles_for(words);
     switch (scan_iters_for(words)) {
         case 2:
             hipLaunchKernelGGL((scan_lookback_kernel<2>), dim3(tiles), dim3(kScanBlock), 0, stream, d_mask, words,
-                               tile_state, glob, d_prefix, d_total_out);
+                               s.tile_state, s.glob, d_prefix, d_total_out, expect_total, s.status, s.scan_spin_limit);
             break;
         case 4:
             hipLaunchKernelGGL((scan_lookback_kernel<4>), dim3(tiles), dim3(kScanBlock), 0, stream, d_mask, words,
-                               tile_state, glob, d_prefix, d_total_out);
+                               s.tile_state, s.glob, d_prefix, d_total_out, expect_total, s.status, s.scan_spin_limit);
             break;
         default:
             hipLaunchKernelGGL((scan_lookback_kernel<16>), dim3(tiles), dim3(kScanBlock), 0, stream, d_mask, words,
-                               tile_state, glob, d_prefix, d_total_out);
+                               s.tile_state, s.glob, d_prefix, d_total_out, expect_total, s.status, s.scan_spin_limit);
     }
+}
+
+__global__ void status_read_kernel(uint32_t* status, uint32_t* out, uint32_t clear) {
+    const uint32_t v = clear ? atomicExch(status, 0u) : __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (out != nullptr) *out = v;
 }
 
 // Workgroups of a persistent kernel that fit on the device at once.
@@ -1298,21 +1321,27 @@ hipError_t prepare_mask_kernels() {
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kSmallScope * sizeof(uint32_t)));
 }
 
+uint32_t mask_hist_blocks(int num_cu) { return resident_blocks(hist0_kernel<true>, kHistBlock, num_cu, 2); }
+
+hipError_t launch_status_read(uint32_t* d_status, uint32_t* d_out, bool clear, hipStream_t stream) {
+    hipLaunchKernelGGL(status_read_kernel, dim3(1), dim3(1), 0, stream, d_status, d_out, clear ? 1u : 0u);
+    return hipGetLastError();
+}
+
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
                              uint64_t sampled_elems, bool any_sampled, uint32_t max_tiny, uint32_t max_small,
-                             bool table_changed, unsigned long long* d_mask, uint32_t* d_prefix, int num_cu,
-                             hipStream_t stream) {
+                             bool fresh_table, unsigned long long* d_mask, uint32_t* d_prefix,
+                             unsigned long long expect_total, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     const uint32_t words = div_up_u64(n, 64);
     const bool aligned = (reinterpret_cast<uintptr_t>(d_weights) & 15u) == 0;
     const uint32_t hist_tiles = div_up_u64(n, kHistTile), emit_tiles = div_up_u64(n, kEmitTile);
 
-    if (table_changed && nseg > 1)
+    if (fresh_table && nseg > 1)
         hipLaunchKernelGGL(tile_scope_kernel, dim3(div_up_u64(emit_tiles, 256)), dim3(256), 0, stream, s.seg, nseg,
                            emit_tiles, s.tile_scope);
 
-    static const uint32_t hist_want = resident_blocks(hist0_kernel<true>, kHistBlock, num_cu, 2);
-    const uint32_t hist_grid = hist_tiles < hist_want ? hist_tiles : hist_want;
+    const uint32_t hist_grid = hist_tiles < s.hist_blocks ? hist_tiles : s.hist_blocks;
     // a record takes what the candidate capacity allows per tile (all of its slots unless a test lowered it)
     const uint32_t per_tile = (uint32_t)(s.cand_cap / emit_tiles);
     const uint32_t rec_cap = per_tile < kRecSlots - 1 ? per_tile : kRecSlots - 1;
@@ -1359,11 +1388,11 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
         hipLaunchKernelGGL(count1_kernel, dim3(count_grid), dim3(kCountBlock), 0, stream, d_weights, n, s.seg, nseg,
                            s.state, s.glob, s.tile_scope, s.rec, s.hist1, s.kept_above, pass);
         hipLaunchKernelGGL(select1_kernel, dim3(nseg), dim3(kDigit1Bins / 16), 0, stream, s.seg, s.state, s.hist1,
-                           s.kept_above, s.glob, pass);
+                           s.kept_above, s.glob, s.status, pass);
     }
 
     hipLaunchKernelGGL(compact2_kernel, dim3(kMatchBlocks), dim3(kListBlock), 0, stream, d_weights, n, s.seg, nseg,
-                       s.state, s.glob, s.tile_scope, s.rec, s.match, s.match_count);
+                       s.state, s.glob, s.tile_scope, s.rec, s.match, s.match_count, s.status);
     hipLaunchKernelGGL(final_kernel, dim3(nseg), dim3(kFinalBlock), 0, stream, d_weights, s.seg, s.state, s.glob,
                        s.match, s.match_count);
     const uint32_t scan_tiles = scan_tiles_for(words);
@@ -1373,17 +1402,21 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
         hipError_t r = hipStreamWaitEvent(stream, s.join_event, 0);
         if (r != hipSuccess) return r;
     }
-    launch_scan(d_mask, words, s.tile_state, s.glob, d_prefix, static_cast<u64*>(nullptr), stream);
+    launch_scan(s, d_mask, words, d_prefix, static_cast<u64*>(nullptr), expect_total, stream);
     return hipGetLastError();
 }
 
+static_assert(scan_tile_words(2) * 128 >= (1u << 19) && scan_tile_words(4) * 512 >= (1u << 22) &&
+              (u64)scan_tile_words(16) * kScanMaxTiles >= (1ull << 26), "no mask below 2^32 bits needs more than kScanMaxTiles tiles");
+
 hipError_t launch_prefix_scan(const MaskScratch& s, const unsigned long long* d_mask, uint32_t words,
-                              uint32_t* d_prefix, unsigned long long* d_total_out, hipStream_t stream) {
+                              uint32_t* d_prefix, unsigned long long* d_total_out, bool reset_status,
+                              hipStream_t stream) {
     if (words == 0) return hipSuccess;
     const uint32_t scan_tiles = scan_tiles_for(words);
     hipLaunchKernelGGL(scan_reset_kernel, dim3(div_up_u64(scan_tiles + 1, 256)), dim3(256), 0, stream, s.tile_state,
-                       scan_tiles, s.glob);
-    launch_scan(d_mask, words, s.tile_state, s.glob, d_prefix, d_total_out, stream);
+                       scan_tiles, s.glob, reset_status ? s.status : static_cast<uint32_t*>(nullptr));
+    launch_scan(s, d_mask, words, d_prefix, d_total_out, kNoExpectedTotal, stream);
     return hipGetLastError();
 }
 

@@ -20,6 +20,14 @@ struct Chunk {
 
 __device__ __forceinline__ uint32_t popc64(unsigned long long x) { return (uint32_t)__popcll(x); }
 
+// Called by one thread of the workgroup that holds the end of the tensor: the mask's own bit count
+// (last prefix entry + bits of the last word) against the nnz the caller passed.
+__device__ __forceinline__ void check_total(const unsigned long long* __restrict__ mask,
+                                            const uint32_t* __restrict__ prefix, uint32_t words, uint32_t nnz,
+                                            uint32_t* __restrict__ status) {
+    if (prefix[words - 1] + popc64(mask[words - 1]) != nnz) atomicOr(status, kDevCountMismatch);
+}
+
 // Sub-mask and first compact slot of chunk q (kElems elements starting at q * kElems).
 template <typename T>
 __device__ __forceinline__ void chunk_meta(uint32_t q, unsigned long long word, uint32_t pre,
@@ -102,7 +110,8 @@ template <typename T, int U>
 __global__ __launch_bounds__(kCompressBlock, 8) void compress_tile_kernel(const u32x4* __restrict__ grad, uint32_t n,
                                                                        const unsigned long long* __restrict__ mask,
                                                                        const uint32_t* __restrict__ prefix,
-                                                                       T* __restrict__ compact, uint32_t nnz) {
+                                                                       T* __restrict__ compact, uint32_t nnz,
+                                                                       uint32_t* __restrict__ status) {
     typedef BlockTile<T, U> G;
     constexpr uint32_t E = G::E;
     __shared__ __attribute__((aligned(16))) T stage[G::kStage];
@@ -133,9 +142,14 @@ __global__ __launch_bounds__(kCompressBlock, 8) void compress_tile_kernel(const 
     const uint32_t w1 = w0 + G::kWords;
     const uint32_t s0 = prefix[w0];
     const uint32_t s1 = w1 < words ? prefix[w1] : nnz;
+    if (tile == gridDim.x - 1 && threadIdx.x == 0) check_total(mask, prefix, words, nnz, status);
     // A mask/prefix/nnz triple that does not fit together must not make the kernel write out of
-    // bounds.  (Same decision in every thread, so the barrier below is safe.)
-    if (s0 > s1 || s1 > nnz || s1 - s0 > G::kElems) return;
+    // bounds: the tile is skipped and the status word says so.  (Same decision in every thread, so
+    // the barrier below is safe.)
+    if (s0 > s1 || s1 > nnz || s1 - s0 > G::kElems) {
+        if (threadIdx.x == 0) atomicOr(status, kDevMetaMismatch);
+        return;
+    }
     const uint32_t count = s1 - s0;
     const uint32_t ph = phase_of(compact + s0);
 
@@ -191,14 +205,17 @@ template <typename T>
 __global__ __launch_bounds__(kBlock) void compress_scalar_kernel(const T* __restrict__ grad, uint32_t n,
                                                                  const unsigned long long* __restrict__ mask,
                                                                  const uint32_t* __restrict__ prefix,
-                                                                 T* __restrict__ compact, uint32_t nnz) {
+                                                                 T* __restrict__ compact, uint32_t nnz,
+                                                                 uint32_t* __restrict__ status) {
     const unsigned long long i = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
     if (i >= n) return;
+    if (i == n - 1) check_total(mask, prefix, (uint32_t)(((unsigned long long)n + 63) >> 6), nnz, status);
     const unsigned long long wd = mask[i >> 6];
     const uint32_t b = (uint32_t)i & 63u;
     if ((wd >> b) & 1ull) {
         const uint32_t slot = prefix[i >> 6] + popc64(wd & ((1ull << b) - 1ull));
         if (slot < nnz) compact[slot] = grad[i];
+        else atomicOr(status, kDevMetaMismatch);
     }
 }
 
@@ -231,7 +248,8 @@ template <typename T, int U>
 __global__ __launch_bounds__(kPackBlock) void decompress_tile_kernel(const T* __restrict__ compact, uint32_t nnz,
                                                                      const unsigned long long* __restrict__ mask,
                                                                      const uint32_t* __restrict__ prefix,
-                                                                     u32x4* __restrict__ dense, uint32_t n) {
+                                                                     u32x4* __restrict__ dense, uint32_t n,
+                                                                     uint32_t* __restrict__ status) {
     typedef Tile<T, U> G;
     constexpr uint32_t E = G::E;
     __shared__ __attribute__((aligned(16))) T stage[kPackWaves][G::kStage];
@@ -262,8 +280,12 @@ __global__ __launch_bounds__(kPackBlock) void decompress_tile_kernel(const T* __
     const uint32_t w1 = w0 + G::kWords;
     const uint32_t s0 = prefix[w0];
     const uint32_t s1 = w1 < words ? prefix[w1] : nnz;
-    // Inconsistent metadata: read nothing, the tile's outputs become zero.
+    // Inconsistent metadata: read nothing, the tile's outputs become zero, the status word says so.
     const bool sane = s0 <= s1 && s1 <= nnz && s1 - s0 <= G::kElems;
+    if (lane == 0) {
+        if (!sane) atomicOr(status, kDevMetaMismatch);
+        if (w1 >= words) check_total(mask, prefix, words, nnz, status);   // the tile that holds the end
+    }
     const uint32_t count = sane ? s1 - s0 : 0u;
     const uint32_t ph = phase_of(compact + s0);
     T* my = stage[wave];
@@ -312,15 +334,18 @@ template <typename T>
 __global__ __launch_bounds__(kBlock) void decompress_scalar_kernel(const T* __restrict__ compact, uint32_t nnz,
                                                                    const unsigned long long* __restrict__ mask,
                                                                    const uint32_t* __restrict__ prefix,
-                                                                   T* __restrict__ dense, uint32_t n) {
+                                                                   T* __restrict__ dense, uint32_t n,
+                                                                   uint32_t* __restrict__ status) {
     const unsigned long long i = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
     if (i >= n) return;
+    if (i == n - 1) check_total(mask, prefix, (uint32_t)(((unsigned long long)n + 63) >> 6), nnz, status);
     const unsigned long long wd = mask[i >> 6];
     const uint32_t b = (uint32_t)i & 63u;
     T val = 0;
     if ((wd >> b) & 1ull) {
         const uint32_t slot = prefix[i >> 6] + popc64(wd & ((1ull << b) - 1ull));
         if (slot < nnz) val = compact[slot];
+        else atomicOr(status, kDevMetaMismatch);
     }
     dense[i] = val;
 }
@@ -352,7 +377,8 @@ template <typename T, int U>
 __global__ __launch_bounds__(kPackBlock) void update_tile_kernel(const T* __restrict__ compact, uint32_t nnz,
                                                                  const unsigned long long* __restrict__ mask,
                                                                  const uint32_t* __restrict__ prefix, float alpha,
-                                                                 u32x4* __restrict__ weights, uint32_t n) {
+                                                                 u32x4* __restrict__ weights, uint32_t n,
+                                                                 uint32_t* __restrict__ status) {
     typedef UpdateTile<T, U> G;
     constexpr uint32_t E = G::E, EC = G::EC;
     __shared__ __attribute__((aligned(16))) T stage[kPackWaves][G::kStage];
@@ -388,6 +414,10 @@ __global__ __launch_bounds__(kPackBlock) void update_tile_kernel(const T* __rest
     const uint32_t s1 = w1 < words ? prefix[w1] : nnz;
     // Inconsistent metadata: read no compact value, kept weights of the tile stay as they are.
     const bool sane = s0 <= s1 && s1 <= nnz && s1 - s0 <= G::kElems;
+    if (lane == 0) {
+        if (!sane) atomicOr(status, kDevMetaMismatch);
+        if (w1 >= words) check_total(mask, prefix, words, nnz, status);   // the tile that holds the end
+    }
     const uint32_t count = sane ? s1 - s0 : 0u;
     const uint32_t ph = phase_of(compact + s0);
     T* my = stage[wave];
@@ -449,14 +479,17 @@ template <typename T>
 __global__ __launch_bounds__(kBlock) void update_scalar_kernel(const T* __restrict__ compact, uint32_t nnz,
                                                                const unsigned long long* __restrict__ mask,
                                                                const uint32_t* __restrict__ prefix, float alpha,
-                                                               float* __restrict__ weights, uint32_t n) {
+                                                               float* __restrict__ weights, uint32_t n,
+                                                               uint32_t* __restrict__ status) {
     const unsigned long long i = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
     if (i >= n) return;
+    if (i == n - 1) check_total(mask, prefix, (uint32_t)(((unsigned long long)n + 63) >> 6), nnz, status);
     const unsigned long long wd = mask[i >> 6];
     const uint32_t b = (uint32_t)i & 63u;
     float val = 0.0f;
     if ((wd >> b) & 1ull) {
         const uint32_t slot = prefix[i >> 6] + popc64(wd & ((1ull << b) - 1ull));
+        if (slot >= nnz) atomicOr(status, kDevMetaMismatch);
         const float g = slot < nnz ? widen<T>(compact[slot]) : 0.0f;
         val = __fsub_rn(weights[i], __fmul_rn(alpha, g));
     }
@@ -579,85 +612,87 @@ inline uint32_t div_up(unsigned long long a, unsigned long long b) { return (uin
 }  // namespace
 
 hipError_t launch_compress(const void* d_grad, int dtype, uint32_t n, const unsigned long long* d_mask,
-                           const uint32_t* d_prefix, void* d_compact, uint32_t nnz, hipStream_t stream) {
+                           const uint32_t* d_prefix, void* d_compact, uint32_t nnz, uint32_t* d_status,
+                           hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (aligned16(d_grad)) {
         if (dtype == 0) {
             const uint32_t tiles = div_up(n, BlockTile<uint32_t, kCompressU>::kElems);
             hipLaunchKernelGGL((compress_tile_kernel<uint32_t, kCompressU>), dim3(tiles), dim3(kCompressBlock), 0,
                                stream, static_cast<const u32x4*>(d_grad), n, d_mask, d_prefix,
-                               static_cast<uint32_t*>(d_compact), nnz);
+                               static_cast<uint32_t*>(d_compact), nnz, d_status);
         } else {
             const uint32_t tiles = div_up(n, BlockTile<uint16_t, kCompressU>::kElems);
             hipLaunchKernelGGL((compress_tile_kernel<uint16_t, kCompressU>), dim3(tiles), dim3(kCompressBlock), 0,
                                stream, static_cast<const u32x4*>(d_grad), n, d_mask, d_prefix,
-                               static_cast<uint16_t*>(d_compact), nnz);
+                               static_cast<uint16_t*>(d_compact), nnz, d_status);
         }
     } else {
         const uint32_t blocks = div_up(n, kBlock);
         if (dtype == 0)
             hipLaunchKernelGGL((compress_scalar_kernel<uint32_t>), dim3(blocks), dim3(kBlock), 0, stream,
                                static_cast<const uint32_t*>(d_grad), n, d_mask, d_prefix,
-                               static_cast<uint32_t*>(d_compact), nnz);
+                               static_cast<uint32_t*>(d_compact), nnz, d_status);
         else
             hipLaunchKernelGGL((compress_scalar_kernel<uint16_t>), dim3(blocks), dim3(kBlock), 0, stream,
                                static_cast<const uint16_t*>(d_grad), n, d_mask, d_prefix,
-                               static_cast<uint16_t*>(d_compact), nnz);
+                               static_cast<uint16_t*>(d_compact), nnz, d_status);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_decompress(const void* d_compact, int dtype, uint32_t nnz, const unsigned long long* d_mask,
-                             const uint32_t* d_prefix, void* d_dense, uint32_t n, hipStream_t stream) {
+                             const uint32_t* d_prefix, void* d_dense, uint32_t n, uint32_t* d_status,
+                             hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (aligned16(d_dense)) {
         if (dtype == 0) {
             const uint32_t tiles = div_up(n, Tile<uint32_t, kPackU>::kElems);
             hipLaunchKernelGGL((decompress_tile_kernel<uint32_t, kPackU>), dim3(div_up(tiles, kPackWaves)),
                                dim3(kPackBlock), 0, stream, static_cast<const uint32_t*>(d_compact), nnz, d_mask,
-                               d_prefix, static_cast<u32x4*>(d_dense), n);
+                               d_prefix, static_cast<u32x4*>(d_dense), n, d_status);
         } else {
             const uint32_t tiles = div_up(n, Tile<uint16_t, kPackU>::kElems);
             hipLaunchKernelGGL((decompress_tile_kernel<uint16_t, kPackU>), dim3(div_up(tiles, kPackWaves)),
                                dim3(kPackBlock), 0, stream, static_cast<const uint16_t*>(d_compact), nnz, d_mask,
-                               d_prefix, static_cast<u32x4*>(d_dense), n);
+                               d_prefix, static_cast<u32x4*>(d_dense), n, d_status);
         }
     } else {
         const uint32_t blocks = div_up(n, kBlock);
         if (dtype == 0)
             hipLaunchKernelGGL((decompress_scalar_kernel<uint32_t>), dim3(blocks), dim3(kBlock), 0, stream,
                                static_cast<const uint32_t*>(d_compact), nnz, d_mask, d_prefix,
-                               static_cast<uint32_t*>(d_dense), n);
+                               static_cast<uint32_t*>(d_dense), n, d_status);
         else
             hipLaunchKernelGGL((decompress_scalar_kernel<uint16_t>), dim3(blocks), dim3(kBlock), 0, stream,
                                static_cast<const uint16_t*>(d_compact), nnz, d_mask, d_prefix,
-                               static_cast<uint16_t*>(d_dense), n);
+                               static_cast<uint16_t*>(d_dense), n, d_status);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_decompress_update(const void* d_compact, int dtype, uint32_t nnz, const unsigned long long* d_mask,
                                     const uint32_t* d_prefix, float alpha, float* d_weights, uint32_t n,
-                                    hipStream_t stream) {
+                                    uint32_t* d_status, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (aligned16(d_weights)) {
         const uint32_t tiles = div_up(n, UpdateTile<uint32_t, kPackU>::kElems);   // same for both payload types
         if (dtype == 0)
             hipLaunchKernelGGL((update_tile_kernel<uint32_t, kPackU>), dim3(div_up(tiles, kPackWaves)), dim3(kPackBlock),
                                0, stream, static_cast<const uint32_t*>(d_compact), nnz, d_mask, d_prefix, alpha,
-                               reinterpret_cast<u32x4*>(d_weights), n);
+                               reinterpret_cast<u32x4*>(d_weights), n, d_status);
         else
             hipLaunchKernelGGL((update_tile_kernel<uint16_t, kPackU>), dim3(div_up(tiles, kPackWaves)), dim3(kPackBlock),
                                0, stream, static_cast<const uint16_t*>(d_compact), nnz, d_mask, d_prefix, alpha,
-                               reinterpret_cast<u32x4*>(d_weights), n);
+                               reinterpret_cast<u32x4*>(d_weights), n, d_status);
     } else {
         const uint32_t blocks = div_up(n, kBlock);
         if (dtype == 0)
             hipLaunchKernelGGL((update_scalar_kernel<uint32_t>), dim3(blocks), dim3(kBlock), 0, stream,
-                               static_cast<const uint32_t*>(d_compact), nnz, d_mask, d_prefix, alpha, d_weights, n);
+                               static_cast<const uint32_t*>(d_compact), nnz, d_mask, d_prefix, alpha, d_weights, n, d_status);
         else
             hipLaunchKernelGGL((update_scalar_kernel<uint16_t>), dim3(blocks), dim3(kBlock), 0, stream,
-                               static_cast<const uint16_t*>(d_compact), nnz, d_mask, d_prefix, alpha, d_weights, n);
+                               static_cast<const uint16_t*>(d_compact), nnz, d_mask, d_prefix, alpha, d_weights, n, d_status);
     }
     return hipGetLastError();
 }

@@ -1,4 +1,4 @@
-// Ternary payload (Sec. III-D "Pruning with Gradient Quantization"): the TernGrad quantiser on the
+// Ternary payload (Sec. III-D): the TernGrad quantiser on the
 // compact buffer.  Shared scale s = max |g| over the workers' buffers; element -> s * sign(g) * b,
 // b ~ Bernoulli(|g| / s); 2-bit codes, four per byte; the workers' ternaries are summed as integers.
 // Random bits come from the Philox4x32-10 counter-based generator (Salmon et al., SC'11):

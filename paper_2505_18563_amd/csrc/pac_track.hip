@@ -1,7 +1,6 @@
-// Mask Tracker kernels (Sec. III-B "Mask Tracker mechanism"; Alg. 1 "update sparse mask using Mask
-// Tracker"): the mask of the non-zero elements of a flat tensor (the Weight != 0 of Eq. 2), the
-// comparison of two masks, and the stability counter.  All are streaming passes over n*e or n/8
-// bytes and are bound by HBM bandwidth.
+// Mask Tracker kernels (Sec. III-B, Mask Tracker paragraph; Alg. 1, mask-update step): the mask of
+// the non-zero elements of a flat tensor (the Weight != 0 of Eq. 2), the comparison of two masks, and
+// the stability counter.  All are streaming passes over n*e or n/8 bytes, bound by HBM bandwidth.
 #include "pac_internal.h"
 
 namespace pac {

@@ -103,3 +103,91 @@ def test_two_contexts_on_two_streams_do_not_interfere():
     finally:
         for c in ctxs:
             c.close()
+
+
+
+def test_cyclic_sparsity_schedule_keeps_its_tables_resident_and_replays_from_graphs():
+    """The per-layer schedule of the largest workload changes the scope table every step (s = 0.5, 0.8, 0.95
+    in turn).  The context keeps the last few tables on the device, so after one eager round every step of
+    the cycle enqueues kernels only: each is captured in a graph of its own and replayed, twice round the
+    cycle with fresh inputs, against the oracle.  A table the context has not seen is refused under capture."""
+    import oracle
+    import paper_2505_18563_amd as pac
+    dev = torch.device("cuda", 0)
+    wl = make_workload(5, device=dev, reduced=True, workers=2)
+    n, W = wl.n, wl.workers
+    nseg = len(wl.scope_offsets) - 1
+    ctx = pac.PacContext(max_elems=n, max_segments=nseg, device=0)
+    try:
+        h = ctx.handle
+        words = (n + 63) // 64
+        cycle = [wl.sparsity_at(t) for t in range(3)]
+        ks = [sum(pac.pac_keep_count(wl.scope_offsets[i + 1] - wl.scope_offsets[i], sp[i]) for i in range(nseg)) for sp in cycle]
+        weights = wl.weights.clone()
+        grads = [g.clone() for g in wl.grads]
+        mask = torch.empty(words, dtype=torch.int64, device=dev)
+        prefix = torch.empty(words, dtype=torch.int32, device=dev)
+        compact = [torch.empty(max(ks), dtype=torch.float32, device=dev) for _ in range(W)]
+        red = torch.empty(max(ks), dtype=torch.float32, device=dev)
+        dense = torch.empty(n, dtype=torch.float32, device=dev)
+
+        def step(t):
+            nnz = pac.pac_build_mask(h, weights, wl.scope_offsets, cycle[t], mask, prefix)
+            for w in range(W):
+                pac.pac_compress(h, grads[w], mask, prefix, compact[w], nnz)
+            pac.pac_reduce_local(h, compact, red, nnz)
+            pac.pac_decompress(h, red, mask, prefix, dense, nnz)
+
+        for t in range(3):                       # one eager round: the three tables become resident
+            step(t)
+        torch.cuda.synchronize()
+        graphs = []
+        for t in range(3):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(t)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+        # a table that is not resident cannot be uploaded under capture: refused, nothing enqueued
+        g = torch.cuda.CUDAGraph()
+        refused = None
+        with torch.cuda.graph(g):
+            try:
+                pac.pac_build_mask(h, weights, wl.scope_offsets, [0.25] * nseg, mask, prefix)
+            except pac.PacError as e:
+                refused = e
+        torch.cuda.synchronize()
+        assert refused is not None and refused.status == -1
+        del g
+
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(99)
+        for rnd in range(2):
+            for t in range(3):
+                weights.copy_(torch.randn(n, device=dev, generator=gen) * 0.02)
+                for gr in grads:
+                    gr.copy_(torch.randn(n, device=dev, generator=gen))
+                mask.zero_(); prefix.zero_(); red.zero_(); dense.zero_()
+                torch.cuda.synchronize()
+                graphs[t].replay()
+                torch.cuda.synchronize()
+                em, ep, k = oracle.build_mask(weights.cpu().numpy(), wl.scope_offsets, cycle[t])
+                assert k == ks[t]
+                assert np.array_equal(mask.cpu().numpy().view(np.uint64), em), f"round {rnd} step {t}: mask"
+                assert np.array_equal(prefix.cpu().numpy().view(np.uint32), ep), f"round {rnd} step {t}: prefix"
+                e_red = oracle.reduce_local([oracle.compress(gr.cpu().numpy(), em, k) for gr in grads])
+                assert np.array_equal(red[:k].cpu().numpy().view(np.uint32), e_red.view(np.uint32))
+                e_out = oracle.decompress(e_red, em, n)
+                assert np.array_equal(dense.cpu().numpy().view(np.uint32), e_out.view(np.uint32))
+        assert ctx.device_status() & pac.PAC_DEV_ERROR_MASK == 0
+
+        # more distinct tables than slots, eagerly: the oldest is replaced, results stay right
+        for s in (0.1, 0.2, 0.3, 0.4, 0.6, 0.1):
+            nnz = pac.pac_build_mask(h, weights, wl.scope_offsets, [s] * nseg, mask, prefix)
+            torch.cuda.synchronize()
+            em, ep, k = oracle.build_mask(weights.cpu().numpy(), wl.scope_offsets, [s] * nseg)
+            assert k == nnz and np.array_equal(mask.cpu().numpy().view(np.uint64), em)
+            assert np.array_equal(prefix.cpu().numpy().view(np.uint32), ep)
+    finally:
+        ctx.close()
