@@ -178,6 +178,25 @@ pac_status pac_mask_from_nonzero(pac_ctx* ctx, const void* d_values, pac_dtype d
                                  uint64_t* d_mask, uint32_t* d_prefix, uint64_t* d_nnz_out,
                                  void* hip_stream);
 
+/* pac_mask_from_nonzero for callers that cannot allocate device memory or create a context: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same outputs as
+ * pac_mask_from_nonzero, bit for bit.  It takes no context; the scratch of its prefix scan is a 32 KiB
+ * array inside the library's device image, which every GPU the library runs on holds until the process
+ * ends.  The call allocates nothing, frees nothing and never waits for the device.
+ *   - Runs on the CURRENT HIP device; every pointer must belong to it.
+ *   - n at most 2^32 - 1 (PAC_ERR_RANGE beyond; the array is sized for that maximum).
+ *   - d_flags_out (DEVICE uint32, may be NULL) receives this call's PAC_DEV_* bits (only
+ *     PAC_DEV_SCAN_STALLED can occur), in stream order.
+ *   - All calls on one GPU share the one array, which keeps the last call's contents (each call clears
+ *     what it needs first, on the stream): calls that may run at the same time on one GPU - from two
+ *     streams or two threads - race; issue them on one stream, or order the streams with events.
+ *   - The first call on a device looks up the array's address (no allocation); make that call, with
+ *     any n, n = 0 included, before capturing a stream.
+ * Error text: pac_last_error(NULL), per thread. */
+pac_status pac_mask_from_nonzero_noalloc(const void* d_values, pac_dtype dtype, uint64_t n, uint64_t* d_mask,
+                                         uint32_t* d_prefix, uint64_t* d_nnz_out, uint32_t* d_flags_out,
+                                         void* hip_stream);
+
 /* Mask Tracker comparison (Sec. III-B: the mask of this iteration against the previous one):
  * *d_diff_bits_out (DEVICE) = number of positions below n at which the two bitmasks differ;
  * 0 means the sparsity pattern is unchanged.  Bits at and beyond n are ignored. */

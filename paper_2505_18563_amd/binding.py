@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.pac_device_status.argtypes = [vp, vp, ctypes.POINTER(u32), ctypes.c_int, vp]
     lib.pac_mask_from_nonzero.restype = i32
     lib.pac_mask_from_nonzero.argtypes = [vp, vp, i32, u64, vp, vp, vp, vp]
+    lib.pac_mask_from_nonzero_noalloc.restype = i32
+    lib.pac_mask_from_nonzero_noalloc.argtypes = [vp, i32, u64, vp, vp, vp, vp, vp]
     lib.pac_mask_equal.restype = i32
     lib.pac_mask_equal.argtypes = [vp, vp, vp, u64, vp, vp]
     lib.pac_tracker_create.restype = i32
@@ -249,6 +251,28 @@ def pac_mask_from_nonzero(ctx, values: torch.Tensor, mask: torch.Tensor, prefix:
     st = load_library().pac_mask_from_nonzero(ctx, _dev_ptr(values) if n else 0, dt, n, _dev_ptr(mask) if n else 0,
                                               _dev_ptr(prefix) if n else 0, _dev_ptr(nnz_out), _stream_ptr(stream))
     _check(ctx, st)
+
+
+def pac_mask_from_nonzero_noalloc(values: torch.Tensor, mask: torch.Tensor, prefix: torch.Tensor,
+                                  nnz_out: Optional[torch.Tensor] = None, flags_out: Optional[torch.Tensor] = None,
+                                  stream=None) -> None:
+    """pac_mask_from_nonzero without a context and without any allocation, on the current device.
+    nnz_out: device int64 [1]; flags_out: device int32 [1]."""
+    dt = _dtype_code(values)
+    n = values.numel()
+    words = (n + 63) // 64
+    if mask.dtype != torch.int64 or prefix.dtype != torch.int32:
+        raise TypeError("mask must be int64 and prefix int32")
+    if mask.numel() < words or prefix.numel() < words:
+        raise ValueError("mask/prefix too short")
+    if nnz_out is not None and (nnz_out.dtype != torch.int64 or nnz_out.numel() < 1):
+        raise TypeError("nnz_out must be an int64 tensor")
+    if flags_out is not None and (flags_out.dtype != torch.int32 or flags_out.numel() < 1):
+        raise TypeError("flags_out must be an int32 tensor")
+    st = load_library().pac_mask_from_nonzero_noalloc(_dev_ptr(values) if n else 0, dt, n, _dev_ptr(mask) if n else 0,
+                                                      _dev_ptr(prefix) if n else 0, _dev_ptr(nnz_out),
+                                                      _dev_ptr(flags_out), _stream_ptr(stream))
+    _check(None, st)
 
 
 def pac_mask_equal(ctx, mask_a: torch.Tensor, mask_b: torch.Tensor, n: int, diff_out: torch.Tensor,

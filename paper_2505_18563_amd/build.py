@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpactrain.so")
-SOURCES = ["pac_api.hip", "pac_mask.hip", "pac_pack.hip", "pac_track.hip", "pac_ternary.hip"]
+SOURCES = ["pac_api.hip", "pac_mask.hip", "pac_pack.hip", "pac_track.hip", "pac_ternary.hip", "pac_noalloc.hip"]
 HEADERS = [os.path.join(CSRC, "pac_internal.h"), os.path.join(HERE, "..", "include", "pactrain.h")]
 
 HIPCC_FLAGS = [
