@@ -3,9 +3,11 @@
 
 One step = pac_build_mask -> pac_compress for each of W workers -> pac_reduce_local ->
 pac_decompress over one synthetic gradient set that is resident in HBM before timing starts.
-Prints ONE JSON line: whole-step dense-gradient throughput (W*N*e bytes per step time), the
-roofline figures of the dominant kernel (the gather of pac_compress, timed with events on the
-launch stream inside the timed region), and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line: whole-step dense-gradient throughput (W*N*e bytes per step time) on the
+workload the metric is quoted on, the roofline figures of the dominant kernel (the gather of
+pac_compress, timed with events on the launch stream inside the timed region), the CPU oracle timed
+on a bounded sample (one thread, and all cores), and - outside the timed region - the same step on
+every other workload, the mask build on pruned and on all-equal weights, and the calls around the path.
 """
 from __future__ import annotations
 
@@ -21,15 +23,18 @@ if ROOT not in sys.path:
 
 METRIC = "dense-gradient GB/s through mask+compress+sum+decompress; % of HBM peak"
 HBM_PEAK_GBPS = 8000.0
-TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "compress_c4_hbm_traffic.txt")
+TRAFFIC_SUMMARY = os.path.join("profiles", "compress_c4_hbm_traffic.txt")
+HEADLINE = 4
+OTHERS = (1, 2, 3, 5, 6, 7, 8)
 
 
 def measured_traffic(config_id: int):
     """HBM bytes per pac_compress launch from the committed rocprofv3 counter summary (None if absent or
-    for another workload)."""
-    if config_id != 4 or not os.path.exists(TRAFFIC_SUMMARY):
+    for another workload).  Not measured by this run: the line says where it comes from."""
+    path = os.path.join(ROOT, TRAFFIC_SUMMARY)
+    if config_id != HEADLINE or not os.path.exists(path):
         return None
-    for line in open(TRAFFIC_SUMMARY):
+    for line in open(path):
         if line.startswith("traffic_bytes_per_launch"):
             return int(float(line.split("=")[1].split()[0]))
     return None
@@ -40,13 +45,15 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=4, help="workload id 1..8 (4 = the configuration the metric is quoted on; 6-8 = the paper's own model shapes)")
+    ap.add_argument("--config", type=int, default=HEADLINE,
+                    help="workload id 1..8 of the timed region (4 = the configuration the metric is quoted on; "
+                         "6-8 = the paper's own model shapes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=1 << 28)
     ap.add_argument("--no-around", action="store_true",
-                    help="skip the timings of the calls around the hot path (Mask Tracker, fused update)")
-    ap.add_argument("--graph", action="store_true",
-                    help="also capture one whole step in a HIP graph and time its replays (reported as graph_replay_step)")
+                    help="skip the timings of the calls around the hot path (Mask Tracker, fused update, ternary payload)")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the other workloads and the mask-build variants that are timed after the headline")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed loop: a kernel of known traffic "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -64,8 +71,14 @@ def algorithmic_bytes(n: int, k: int, W: int, e: int) -> dict:
     }
 
 
+def step_bytes(n: int, k: int, W: int, e: int) -> int:
+    a = algorithmic_bytes(n, k, W, e)
+    return a["build_mask"] + W * a["compress"] + a["reduce_local"] + a["decompress"]
+
+
 def cpu_baseline(wl, sample_elems: int):
-    """The oracle, as it stands, on a prefix of the same workload (host cores of this machine)."""
+    """The oracle, as it stands, on a prefix of the same workload (host cores of this machine): the
+    definition-level functions on one thread, then their all-core leg."""
     import numpy as np
     import oracle
 
@@ -90,16 +103,253 @@ def cpu_baseline(wl, sample_elems: int):
     oracle.decompress(red, mask, ns, code)
     t4 = time.perf_counter()
     total = t4 - t0
-    return {
+    single = {
         "value": round(wl.workers * ns * e / total / 1e9, 4),
         "unit": "GB/s",
         "cores": 1,
         "kind": "oracle",
         "sample": f"first {ns} of {wl.n} flat elements as one global prune scope, s={s}, all W={wl.workers} workers, "
                   f"{total:.2f} s single-threaded",
-        "stage_s": {"build_mask": round(t1 - t0, 3), "compress": round(t2 - t1, 3),
-                    "reduce_local": round(t3 - t2, 3), "decompress": round(t4 - t3, 3)},
+        "stage_s": [round(t1 - t0, 3), round(t2 - t1, 3), round(t3 - t2, 3), round(t4 - t3, 3)],
     }
+    del compact, red
+    cores = oracle.mt_threads()
+    oracle.build_mask_mt(w[:1 << 16], [0, 1 << 16], s)      # start the thread team outside the timed region
+    u0 = time.perf_counter()
+    mask2, prefix2, k2 = oracle.build_mask_mt(w, [0, ns], s)
+    u1 = time.perf_counter()
+    compact = [oracle.compress_mt(g, mask2, prefix2, k2, code) for g in grads]
+    u2 = time.perf_counter()
+    red = oracle.reduce_local_mt(compact, code)
+    u3 = time.perf_counter()
+    oracle.decompress_mt(red, mask2, prefix2, ns, code)
+    u4 = time.perf_counter()
+    assert k2 == k and np.array_equal(mask, mask2)
+    all_cores = {
+        "value": round(wl.workers * ns * e / (u4 - u0) / 1e9, 4),
+        "unit": "GB/s",
+        "cores": cores,
+        "kind": "oracle, all-core leg (OpenMP over 64-element words; cores = sched_getaffinity count capped by OMP_NUM_THREADS)",
+        "sample": f"the same sample, {u4 - u0:.2f} s on {cores} threads",
+        "stage_s": [round(u1 - u0, 3), round(u2 - u1, 3), round(u3 - u2, 3), round(u4 - u3, 3)],
+    }
+    return single, all_cores
+
+
+class Bench:
+    """One workload resident on the device with every buffer a step needs."""
+
+    def __init__(self, config_id: int, pac, torch, dev):
+        from synth import make_workload
+        self.pac, self.torch, self.dev = pac, torch, dev
+        self.config_id = config_id
+        wl = self.wl = make_workload(config_id, device=dev)
+        self.n, self.W = wl.n, wl.workers
+        self.e = 4 if wl.dtype == "f32" else 2
+        tdtype = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+        self.nseg = len(wl.scope_offsets) - 1
+        self.schedule = [wl.sparsity_at(t) for t in range(len(wl.sparsity_schedule))]
+        self.k_by_phase = [sum(pac.pac_keep_count(wl.scope_offsets[i + 1] - wl.scope_offsets[i], sp[i])
+                               for i in range(self.nseg)) for sp in self.schedule]
+        kmax = max(self.k_by_phase)
+        self.ctx = pac.PacContext(max_elems=self.n, max_segments=self.nseg, device=0)
+        self.h = self.ctx.handle
+        words = (self.n + 63) // 64
+        self.mask = torch.empty(words, dtype=torch.int64, device=dev)
+        self.prefix = torch.empty(words, dtype=torch.int32, device=dev)
+        self.compact = [torch.empty(kmax, dtype=tdtype, device=dev) for _ in range(self.W)]
+        self.red = torch.empty(kmax, dtype=tdtype, device=dev)
+        self.dense_out = torch.empty(self.n, dtype=tdtype, device=dev)
+        self.ev_pairs = []
+
+    def close(self):
+        self.ctx.close()
+
+    def describe(self) -> str:
+        wl = self.wl
+        return (f"C{self.config_id} {wl.name}: N={self.n} flat elements in {len(wl.specs)} tensors, "
+                f"{wl.scope} prune s={'/'.join(str(s) for s in wl.sparsity_schedule)}, W={self.W} workers, "
+                f"{wl.dtype} payload, mask rebuilt every step")
+
+    def step(self, phase: int, timed: bool = False):
+        pac, h, wl = self.pac, self.h, self.wl
+        nnz = pac.pac_build_mask(h, wl.weights, wl.scope_offsets, self.schedule[phase], self.mask, self.prefix)
+        if timed:
+            a = self.torch.cuda.Event(enable_timing=True)
+            b = self.torch.cuda.Event(enable_timing=True)
+            a.record()
+        for w in range(self.W):
+            pac.pac_compress(h, wl.grads[w], self.mask, self.prefix, self.compact[w], nnz)
+        if timed:
+            b.record()
+            self.ev_pairs.append((a, b))
+        pac.pac_reduce_local(h, self.compact, self.red, nnz)
+        pac.pac_decompress(h, self.red, self.mask, self.prefix, self.dense_out, nnz)
+        return nnz
+
+    def time_call(self, fn, reps=5):
+        """Mean time of fn over reps back-to-back calls, events on the launch stream."""
+        torch = self.torch
+        fn()
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    def stage_ms(self, phase: int = 0) -> dict:
+        pac, h, wl = self.pac, self.h, self.wl
+        sp, nnz = self.schedule[phase], self.k_by_phase[phase]
+        out = {
+            "build_mask": self.time_call(lambda: pac.pac_build_mask(h, wl.weights, wl.scope_offsets, sp, self.mask, self.prefix)),
+            "compress_per_worker": self.time_call(lambda: pac.pac_compress(h, wl.grads[0], self.mask, self.prefix, self.compact[0], nnz)),
+            "reduce_local": self.time_call(lambda: pac.pac_reduce_local(h, self.compact, self.red, nnz)),
+            "decompress": self.time_call(lambda: pac.pac_decompress(h, self.red, self.mask, self.prefix, self.dense_out, nnz)),
+        }
+        return {k: round(v, 4) for k, v in out.items()}
+
+    def cached_mask_step(self, phase: int = 0):
+        pac, h, wl = self.pac, self.h, self.wl
+        nnz = self.k_by_phase[phase]
+        for w in range(self.W):
+            pac.pac_compress(h, wl.grads[w], self.mask, self.prefix, self.compact[w], nnz)
+        pac.pac_reduce_local(h, self.compact, self.red, nnz)
+        pac.pac_decompress(h, self.red, self.mask, self.prefix, self.dense_out, nnz)
+
+    def graph_replay_ms(self, phase: int = 0, reps: int = 20) -> float:
+        """The whole step (mask build included) replayed from a HIP graph."""
+        torch = self.torch
+        self.step(phase)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step(phase)
+        torch.cuda.synchronize()
+        ms = self.time_call(graph.replay, reps=reps)
+        del graph
+        return ms
+
+    def summary(self, phase: int, ms: float) -> dict:
+        alg = step_bytes(self.n, self.k_by_phase[phase], self.W, self.e)
+        return {
+            "ms_per_step": round(ms, 4),
+            "step_algorithmic_GBps": round(alg / (ms * 1e-3) / 1e9, 1),
+            "frac": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        }
+
+
+OTHER_FIELDS = ("per workload (C5: per sparsity of its schedule, then the cycling schedule): ms_per_step = one whole step, "
+                "events on the launch stream; step_algorithmic_GBps and frac (of 8 TB/s) on the step's algorithmic bytes; "
+                "stage_ms = [build_mask, compress per worker, reduce_local, decompress]; graph_ms = the step replayed "
+                "from a HIP graph; status = device status word afterwards")
+
+
+def other_workload(config_id: int, pac, torch, dev) -> dict:
+    """ms per whole step (events on the launch stream, outside the headline's timed region) of another
+    workload, one entry per sparsity of its schedule, with each call's own time."""
+    b = Bench(config_id, pac, torch, dev)
+    try:
+        out = {}
+        reps = 10 if b.n < (1 << 30) else 5
+        for p in range(len(b.schedule)):
+            for _ in range(2):
+                b.step(p)
+            ms = b.time_call(lambda: b.step(p), reps=reps)
+            entry = b.summary(p, ms)
+            entry["stage_ms"] = list(b.stage_ms(p).values())
+            if b.n <= (1 << 24):
+                entry["graph_ms"] = round(b.graph_replay_ms(p), 4)     # what is left without launch overhead
+            name = f"C{config_id}" if len(b.schedule) == 1 else f"C{config_id}@s={b.wl.sparsity_schedule[p]}"
+            out[name] = entry
+        if len(b.schedule) > 1:
+            counter = [0]
+
+            def cyc():
+                b.step(counter[0] % len(b.schedule))
+                counter[0] += 1
+            for _ in range(len(b.schedule)):
+                cyc()
+            out[f"C{config_id}@cycle"] = {"ms_per_step": round(b.time_call(cyc, reps=2 * len(b.schedule)), 4)}
+        st = b.ctx.device_status(clear=True)
+        for v in out.values():
+            v["status"] = st
+        return out
+    finally:
+        b.close()
+        del b
+        torch.cuda.empty_cache()
+
+
+def mask_build_variants(b: Bench) -> dict:
+    """pac_build_mask on the headline workload's weights as drawn, on the weights a training loop holds
+    (pruned positions zeroed by the library's own pac_decompress_update: Eq. 2 keeps them zero), and on one
+    all-equal scope of the same length."""
+    pac, torch, h, wl = b.pac, b.torch, b.h, b.wl
+    sp, nnz = b.schedule[0], b.k_by_phase[0]
+    out = {}
+
+    def build(wts):
+        return lambda: pac.pac_build_mask(h, wts, wl.scope_offsets, sp, b.mask, b.prefix)
+
+    out["as_drawn_ms"] = round(b.time_call(build(wl.weights)), 4)
+    b.ctx.device_status(clear=True)
+    b.step(0)
+    w2 = wl.weights.clone()
+    pac.pac_decompress_update(h, b.red, b.mask, b.prefix, 1e-3, w2, nnz)
+    out["pruned_ms"] = round(b.time_call(build(w2)), 4)
+    out["pruned_device_status"] = b.ctx.device_status(clear=True)
+    w2.fill_(0.02)
+    out["all_equal_ms"] = round(b.time_call(build(w2)), 4)
+    out["all_equal_device_status"] = b.ctx.device_status(clear=True)
+    del w2
+    pac.pac_build_mask(h, wl.weights, wl.scope_offsets, sp, b.mask, b.prefix)
+    return out
+
+
+def around_the_path(b: Bench) -> dict:
+    """Calls around the hot path (Mask Tracker, fused weight update, ternary payload): timed on the same
+    workload, outside the timed region, reported with their own algorithmic bytes."""
+    pac, torch, h, wl, dev = b.pac, b.torch, b.h, b.wl, b.dev
+    n, W, e = b.n, b.W, b.e
+    nnz0 = b.k_by_phase[0]
+    mask, prefix, red, dense_out, compact = b.mask, b.prefix, b.red, b.dense_out, b.compact
+    meta = n // 8 + n // 16
+    nz_out = torch.empty(1, dtype=torch.int64, device=dev)
+    mask2 = torch.empty_like(mask)
+    prefix2 = torch.empty_like(prefix)
+    diff_out = torch.empty(1, dtype=torch.int64, device=dev)
+    state_out = torch.empty(2, dtype=torch.int32, device=dev)
+    pac.pac_decompress(h, red, mask, prefix, dense_out, nnz0)
+    tracker = pac.MaskTracker(b.ctx, max_elems=n, patience=2)
+    w_copy = wl.weights.clone()
+    calls = {
+        "mask_from_nonzero": (lambda: pac.pac_mask_from_nonzero(h, dense_out, mask2, prefix2, nz_out), e * n + meta),
+        "mask_from_nonzero_noalloc": (lambda: pac.pac_mask_from_nonzero_noalloc(dense_out, mask2, prefix2, nz_out), e * n + meta),
+        "mask_equal": (lambda: pac.pac_mask_equal(h, mask, mask2, n, diff_out), 2 * (n // 8)),
+        "tracker_update": (lambda: tracker.update(mask, n, state_out), 3 * (n // 8)),
+        "decompress_update": (lambda: pac.pac_decompress_update(h, red, mask, prefix, 1e-3, w_copy, nnz0),
+                              e * nnz0 + meta + 8 * n),
+    }
+    # ternary payload (Sec. III-D) on the compact buffers of this workload
+    t_scale = torch.zeros(1, dtype=torch.float32, device=dev)
+    t_packed = [torch.empty((nnz0 + 3) // 4, dtype=torch.uint8, device=dev) for _ in range(W)]
+    pac.pac_absmax(h, compact[0], t_scale, count=nnz0)
+    for w in range(W):
+        pac.pac_ternarize(h, compact[w], t_scale, 1, w, t_packed[w], count=nnz0)
+    calls["absmax_per_worker"] = (lambda: pac.pac_absmax(h, compact[0], t_scale, accumulate=True, count=nnz0), e * nnz0)
+    calls["ternarize_per_worker"] = (lambda: pac.pac_ternarize(h, compact[0], t_scale, 1, 0, t_packed[0], count=nnz0),
+                                     e * nnz0 + nnz0 // 4)
+    calls["ternary_reduce_local"] = (lambda: pac.pac_ternary_reduce_local(h, t_packed, t_scale, red, nnz0),
+                                     W * (nnz0 // 4) + e * nnz0)
+    around = {"fields": "[ms per call, GB/s on the call's algorithmic bytes]"}
+    for name, (fn, nbytes) in calls.items():
+        ms = b.time_call(fn)
+        around[name] = [round(ms, 4), round(nbytes / (ms * 1e-3) / 1e9)]
+    tracker.close()
+    return around
 
 
 def main() -> int:
@@ -111,7 +361,6 @@ def main() -> int:
 
     import torch
     import paper_2505_18563_amd as pac
-    from synth import make_workload
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -119,42 +368,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     dev = torch.device("cuda", 0)
 
-    wl = make_workload(args.config, device=dev)
-    n, W = wl.n, wl.workers
-    e = 4 if wl.dtype == "f32" else 2
-    tdtype = torch.float32 if wl.dtype == "f32" else torch.bfloat16
-    nseg = len(wl.scope_offsets) - 1
-    schedule = [wl.sparsity_at(t) for t in range(len(wl.sparsity_schedule))]
-    k_by_phase = [sum(pac.pac_keep_count(wl.scope_offsets[i + 1] - wl.scope_offsets[i], sp[i]) for i in range(nseg))
-                  for sp in schedule]
-    kmax = max(k_by_phase)
-
-    ctx = pac.PacContext(max_elems=n, max_segments=nseg, device=0)
-    words = (n + 63) // 64
-    mask = torch.empty(words, dtype=torch.int64, device=dev)
-    prefix = torch.empty(words, dtype=torch.int32, device=dev)
-    compact = [torch.empty(kmax, dtype=tdtype, device=dev) for _ in range(W)]
-    red = torch.empty(kmax, dtype=tdtype, device=dev)
-    dense_out = torch.empty(n, dtype=tdtype, device=dev)
-    h = ctx.handle
-
-    ev_pairs = []
-
-    def step(t: int, timed: bool):
-        sp = schedule[t % len(schedule)]
-        nnz = pac.pac_build_mask(h, wl.weights, wl.scope_offsets, sp, mask, prefix)
-        if timed:
-            a = torch.cuda.Event(enable_timing=True)
-            b = torch.cuda.Event(enable_timing=True)
-            a.record()
-        for w in range(W):
-            pac.pac_compress(h, wl.grads[w], mask, prefix, compact[w], nnz)
-        if timed:
-            b.record()
-            ev_pairs.append((a, b))
-        pac.pac_reduce_local(h, compact, red, nnz)
-        pac.pac_decompress(h, red, mask, prefix, dense_out, nnz)
-        return nnz
+    b = Bench(args.config, pac, torch, dev)
+    wl, n, W, e = b.wl, b.n, b.W, b.e
+    nphase = len(b.schedule)
 
     if args.pmc_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
@@ -163,106 +379,32 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- the timed region: K whole steps, inputs resident, bracketed by synchronisations ----
     for t in range(args.warmup):
-        step(t, False)
+        b.step(t % nphase)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t in range(args.steps):
-        step(args.warmup + t, True)
+        b.step((args.warmup + t) % nphase, timed=True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     step_s = (t1 - t0) / args.steps
-    compress_ms = sum(a.elapsed_time(b) for a, b in ev_pairs) / (len(ev_pairs) * W)   # per launch
+    compress_ms = sum(a.elapsed_time(c) for a, c in b.ev_pairs) / (len(b.ev_pairs) * W)   # per launch
+    status_after_timed = b.ctx.device_status()
 
-    # per-call times (outside the timed region), events on the launch stream
-    def time_call(fn, reps=5):
-        fn()
-        a = torch.cuda.Event(enable_timing=True)
-        b = torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(reps):
-            fn()
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps
-
-    sp0 = schedule[0]
-    nnz0 = k_by_phase[0]
-    stage_ms = {
-        "build_mask": time_call(lambda: pac.pac_build_mask(h, wl.weights, wl.scope_offsets, sp0, mask, prefix)),
-        "compress_per_worker": time_call(lambda: pac.pac_compress(h, wl.grads[0], mask, prefix, compact[0], nnz0)),
-        "reduce_local": time_call(lambda: pac.pac_reduce_local(h, compact, red, nnz0)),
-        "decompress": time_call(lambda: pac.pac_decompress(h, red, mask, prefix, dense_out, nnz0)),
-    }
-
+    # ---- everything below is outside the timed region and never enters `value` ----
+    stage_ms = b.stage_ms(0)
     # The step a training loop runs while the Mask Tracker reports a stable mask: the mask of the
     # last build is reused, only compress x W, sum and decompress run.
-    def cached_mask_step():
-        for w in range(W):
-            pac.pac_compress(h, wl.grads[w], mask, prefix, compact[w], nnz0)
-        pac.pac_reduce_local(h, compact, red, nnz0)
-        pac.pac_decompress(h, red, mask, prefix, dense_out, nnz0)
+    pac.pac_build_mask(b.h, wl.weights, wl.scope_offsets, b.schedule[0], b.mask, b.prefix)
+    cached_ms = b.time_call(b.cached_mask_step)
+    graph_ms = b.graph_replay_ms(0)
 
-    pac.pac_build_mask(h, wl.weights, wl.scope_offsets, sp0, mask, prefix)
-    cached_ms = time_call(cached_mask_step)
-
-    # The whole step (mask build included) replayed from a HIP graph: what is left of the launch
-    # overhead on the small, launch-bound workloads.
-    graph_ms = None
-    if args.graph:
-        def whole_step():
-            pac.pac_build_mask(h, wl.weights, wl.scope_offsets, sp0, mask, prefix)
-            cached_mask_step()
-        whole_step()
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            whole_step()
-        torch.cuda.synchronize()
-        graph_ms = time_call(graph.replay, reps=20)
-        del graph
-
-    # Calls around the hot path (Mask Tracker, fused weight update): timed on the same workload,
-    # outside the timed region, reported with their own algorithmic bytes.
-    around = {}
-    if not args.no_around:
-        meta = n // 8 + n // 16
-        nz_out = torch.empty(1, dtype=torch.int64, device=dev)
-        mask2 = torch.empty_like(mask)
-        prefix2 = torch.empty_like(prefix)
-        diff_out = torch.empty(1, dtype=torch.int64, device=dev)
-        state_out = torch.empty(2, dtype=torch.int32, device=dev)
-        pac.pac_decompress(h, red, mask, prefix, dense_out, nnz0)
-        tracker = pac.MaskTracker(ctx, max_elems=n, patience=2)
-        w_copy = wl.weights.clone()
-        calls = {
-            "mask_from_nonzero": (lambda: pac.pac_mask_from_nonzero(h, dense_out, mask2, prefix2, nz_out), e * n + meta),
-            "mask_equal": (lambda: pac.pac_mask_equal(h, mask, mask2, n, diff_out), 2 * (n // 8)),
-            "tracker_update": (lambda: tracker.update(mask, n, state_out), 3 * (n // 8)),
-            "decompress_update": (lambda: pac.pac_decompress_update(h, red, mask, prefix, 1e-3, w_copy, nnz0),
-                                  e * nnz0 + meta + 8 * n),
-        }
-        # ternary payload (Sec. III-D) on the compact buffers of this workload
-        t_scale = torch.zeros(1, dtype=torch.float32, device=dev)
-        t_packed = [torch.empty((nnz0 + 3) // 4, dtype=torch.uint8, device=dev) for _ in range(W)]
-        pac.pac_absmax(h, compact[0], t_scale, count=nnz0)
-        for w in range(W):
-            pac.pac_ternarize(h, compact[w], t_scale, 1, w, t_packed[w], count=nnz0)
-        calls["absmax_per_worker"] = (lambda: pac.pac_absmax(h, compact[0], t_scale, accumulate=True, count=nnz0), e * nnz0)
-        calls["ternarize_per_worker"] = (lambda: pac.pac_ternarize(h, compact[0], t_scale, 1, 0, t_packed[0], count=nnz0),
-                                         e * nnz0 + nnz0 // 4)
-        calls["ternary_reduce_local"] = (lambda: pac.pac_ternary_reduce_local(h, t_packed, t_scale, red, nnz0),
-                                         W * (nnz0 // 4) + e * nnz0)
-        for name, (fn, nbytes) in calls.items():
-            ms = time_call(fn)
-            around[name] = {"ms": round(ms, 4), "algorithmic_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
-        tracker.close()
-        del w_copy, mask2, prefix2, t_packed
-
-    k_avg = sum(k_by_phase[(args.warmup + t) % len(schedule)] for t in range(args.steps)) / args.steps
+    k_avg = sum(b.k_by_phase[(args.warmup + t) % nphase] for t in range(args.steps)) / args.steps
     alg = algorithmic_bytes(n, int(k_avg), W, e)
     step_alg = alg["build_mask"] + W * alg["compress"] + alg["reduce_local"] + alg["decompress"]
     achieved = alg["compress"] / (compress_ms * 1e-3) / 1e9
+    traffic = measured_traffic(args.config)
 
     result = {
         "metric": METRIC,
@@ -278,16 +420,16 @@ def main() -> int:
         "dtype": "bf16" if wl.dtype == "bf16" else "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"C{args.config} {wl.name}: N={n} flat elements in {len(wl.specs)} tensors, "
-                        f"{wl.scope} prune s={'/'.join(str(s) for s in wl.sparsity_schedule)}, W={W} workers, "
-                        f"{wl.dtype} payload, mask rebuilt every step",
-            "n_elems": n, "workers": W, "nnz": int(k_avg), "prune_scopes": nseg,
+            "workload": b.describe(),
+            "n_elems": n, "workers": W, "nnz": int(k_avg), "prune_scopes": b.nseg,
         },
         "step_algorithmic_GBps": round(step_alg / step_s / 1e9, 2),
         "step_frac_of_hbm_peak": round(step_alg / step_s / 1e9 / HBM_PEAK_GBPS, 4),
-        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
-        "cached_mask_step": {"ms": round(cached_ms, 4), "value": round(W * n * e / (cached_ms * 1e-3) / 1e9, 2),
-                             "unit": "GB/s", "note": "mask of the last build reused (stable mask): compress x W + sum + decompress"},
+        "stage_ms": stage_ms,
+        "build_mask_algorithmic_GBps": round(alg["build_mask"] / (stage_ms["build_mask"] * 1e-3) / 1e9, 1),
+        "device_status_after_timed_steps": status_after_timed,
+        "cached_mask_step": {"ms": round(cached_ms, 4), "note": "stable mask: the last mask reused, compress x W + sum + decompress"},
+        "graph_replay_step": {"ms": round(graph_ms, 4), "note": "the whole step captured in a HIP graph, 20 replays"},
         "roofline": {
             "kernel": "compress_tile_kernel<unsigned short, 7> (pac_compress)" if wl.dtype == "bf16" else "compress_tile_kernel<unsigned int, 7> (pac_compress)",
             "bound": "hbm",
@@ -295,19 +437,32 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": measured_traffic(args.config),
+            "traffic": traffic,
+            "traffic_source": (f"not measured by this run: from the committed rocprofv3 counter summary {TRAFFIC_SUMMARY}"
+                               if traffic is not None else "no counter summary committed for this workload"),
             "bytes_per_launch": alg["compress"],
             "avg_launch_ms": round(compress_ms, 5),
         },
     }
-    if graph_ms is not None:
-        result["graph_replay_step"] = {"ms": round(graph_ms, 4), "value": round(W * n * e / (graph_ms * 1e-3) / 1e9, 2),
-                                       "unit": "GB/s", "note": "one whole step captured in a HIP graph, 20 replays"}
-    if around:
-        result["around_the_path"] = around
+    if not args.no_others:
+        result["build_mask_variants"] = mask_build_variants(b)
+    if not args.no_around:
+        result["around_the_path"] = around_the_path(b)
+    cpu = None
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_elems)
-    ctx.close()
+        cpu = cpu_baseline(wl, args.cpu_sample_elems)
+    b.close()
+    del b, wl
+    torch.cuda.empty_cache()
+    if not args.no_others:
+        others = {"fields": OTHER_FIELDS}
+        for cid in OTHERS:
+            if cid == args.config:
+                continue
+            others.update(other_workload(cid, pac, torch, dev))
+        result["other_workloads"] = others
+    if cpu is not None:
+        result["cpu_baseline"], result["cpu_baseline_all_cores"] = cpu
     print(json.dumps(result), flush=True)
     return 0
 

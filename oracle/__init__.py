@@ -14,6 +14,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "pac_oracle.cpp")
+_SRC_MT = os.path.join(_HERE, "pac_oracle_mt.cpp")   # the all-core leg of the benchmark's CPU baseline
 _LIB = os.path.join(_HERE, "libpac_oracle.so")
 
 F32 = 0
@@ -22,9 +23,9 @@ BF16 = 1
 
 def build(force: bool = False) -> str:
     """Compile the oracle with the host compiler (no fast-math, no FMA contraction)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["g++", "-std=c++17", "-O2", "-fno-fast-math", "-ffp-contract=off", "-fPIC", "-shared",
-               "-o", _LIB, _SRC]
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_MT)):
+        cmd = ["g++", "-std=c++17", "-O2", "-fno-fast-math", "-ffp-contract=off", "-fPIC", "-shared", "-fopenmp",
+               "-o", _LIB, _SRC, _SRC_MT]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -63,6 +64,16 @@ def _load():
         lib.orc_ternary_reduce.argtypes = [vp, u32, u64, ctypes.c_float, i32, vp]
         lib.orc_decompress_update.restype = u64
         lib.orc_decompress_update.argtypes = [vp, i32, u64, vp, ctypes.c_float, vp, u64]
+        lib.orc_mt_threads.restype = i32
+        lib.orc_mt_threads.argtypes = []
+        lib.orc_build_mask_mt.restype = i32
+        lib.orc_build_mask_mt.argtypes = [vp, u64, vp, u32, vp, vp, vp, vp]
+        lib.orc_compress_mt.restype = None
+        lib.orc_compress_mt.argtypes = [vp, i32, u64, vp, vp, vp]
+        lib.orc_reduce_mt.restype = None
+        lib.orc_reduce_mt.argtypes = [vp, u32, i32, u64, vp]
+        lib.orc_decompress_mt.restype = None
+        lib.orc_decompress_mt.argtypes = [vp, i32, vp, vp, vp, u64]
         _lib = lib
     return _lib
 
@@ -135,6 +146,58 @@ def f32_to_bf16(x: np.ndarray) -> np.ndarray:
     a = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
     out = np.empty(a.size, dtype=np.uint16)
     _load().orc_f32_to_bf16(_ptr(a), _ptr(out), a.size)
+    return out
+
+
+# ---- the all-core leg (pac_oracle_mt.cpp): same results, OpenMP threads over 64-element words ----
+
+def mt_threads() -> int:
+    """Threads the *_mt functions use: the cores the process may run on, capped by OMP_NUM_THREADS."""
+    return int(_load().orc_mt_threads())
+
+
+def build_mask_mt(weights: np.ndarray, seg_offsets=None, sparsity=0.0):
+    w = np.ascontiguousarray(weights, dtype=np.float32).reshape(-1)
+    n = w.size
+    if seg_offsets is None:
+        seg_offsets = [0, n]
+    off = np.ascontiguousarray(seg_offsets, dtype=np.uint64)
+    nseg = off.size - 1
+    sp = np.ascontiguousarray(np.broadcast_to(np.asarray(sparsity, dtype=np.float64), (nseg,)))
+    words = mask_words(n)
+    mask = np.zeros(max(words, 1), dtype=np.uint64)[:words]
+    prefix = np.zeros(max(words, 1), dtype=np.uint32)[:words]
+    nnz = ctypes.c_uint64(0)
+    rc = _load().orc_build_mask_mt(_ptr(w), n, _ptr(off), nseg, _ptr(sp), _ptr(mask), _ptr(prefix),
+                                   ctypes.addressof(nnz))
+    if rc != 0:
+        raise ValueError("orc_build_mask_mt: bad arguments")
+    return mask, prefix, int(nnz.value)
+
+
+def compress_mt(grad: np.ndarray, mask: np.ndarray, prefix: np.ndarray, nnz: int, dtype: int = F32) -> np.ndarray:
+    g = np.ascontiguousarray(grad, dtype=_elem_dtype(dtype)).reshape(-1)
+    out = np.empty(nnz, dtype=_elem_dtype(dtype))
+    _load().orc_compress_mt(_ptr(g), dtype, g.size, _ptr(np.ascontiguousarray(mask)),
+                            _ptr(np.ascontiguousarray(prefix)), _ptr(out))
+    return out
+
+
+def reduce_local_mt(bufs, dtype: int = F32) -> np.ndarray:
+    arrs = [np.ascontiguousarray(b, dtype=_elem_dtype(dtype)).reshape(-1) for b in bufs]
+    nnz = arrs[0].size
+    assert all(a.size == nnz for a in arrs)
+    ptrs = (ctypes.c_void_p * len(arrs))(*[_ptr(a) for a in arrs])
+    out = np.empty(nnz, dtype=_elem_dtype(dtype))
+    _load().orc_reduce_mt(ctypes.addressof(ptrs), len(arrs), dtype, nnz, _ptr(out))
+    return out
+
+
+def decompress_mt(compact: np.ndarray, mask: np.ndarray, prefix: np.ndarray, n: int, dtype: int = F32) -> np.ndarray:
+    c = np.ascontiguousarray(compact, dtype=_elem_dtype(dtype)).reshape(-1)
+    out = np.empty(n, dtype=_elem_dtype(dtype))
+    _load().orc_decompress_mt(_ptr(c), dtype, _ptr(np.ascontiguousarray(mask)), _ptr(np.ascontiguousarray(prefix)),
+                              _ptr(out), n)
     return out
 
 

@@ -352,3 +352,43 @@ def test_pipeline_equals_masked_fold_of_dense_gradients(dtype):
     out = oracle.decompress(red, m, n, dtype)
     out_raw = out.view(np.uint32) if dtype == oracle.F32 else out
     assert np.array_equal(out_raw, np.where(kept, dense_sum, 0))
+
+
+# ---- the all-core leg of the benchmark's CPU baseline: defined by the functions pinned above ----
+
+@pytest.mark.parametrize("trial", range(24))
+def test_all_core_leg_equals_the_definition_oracle(trial):
+    """pac_oracle_mt.cpp (counting select, positional tie rule, word-parallel gather / sum / scatter) against
+    pac_oracle.cpp (composites + nth_element, ascending walks, left fold) on random scope tables, heavy ties,
+    pruned (zeroed) weights, all-equal scopes, empty scopes, s = 0 and s = 1, both payload types."""
+    rng = np.random.default_rng(1000 + trial)
+    n = int(rng.integers(1, 200000)) if trial % 6 else int(rng.integers(1, 130))
+    w = rng.standard_normal(n).astype(np.float32)
+    if trial % 3 == 0:
+        w[rng.random(n) < 0.6] = 0.0
+    if trial % 5 == 0:
+        w[:] = np.float32(0.5)
+    if trial % 7 == 0:
+        w = (np.round(w * 4) / 4).astype(np.float32)
+    if trial % 4 == 1 and n > 8:
+        w[:4] = [np.inf, -np.inf, np.nan, -0.0]
+    nseg = int(rng.integers(1, 9))
+    off = [0] + sorted(int(c) for c in rng.integers(0, n + 1, size=nseg - 1)) + [n]
+    sp = rng.choice([0.0, 1.0, 0.5, 0.9, 0.123456, 0.8], size=nseg)
+    mask, prefix, k = oracle.build_mask(w, off, sp)
+    m2, p2, k2 = oracle.build_mask_mt(w, off, sp)
+    assert k == k2 and np.array_equal(mask, m2) and np.array_equal(prefix, p2)
+    for dt in (oracle.F32, oracle.BF16):
+        W = int(rng.integers(1, 6))
+        if dt == oracle.F32:
+            grads = [rng.standard_normal(n).astype(np.float32) for _ in range(W)]
+        else:
+            grads = [rng.integers(0, 65536, n).astype(np.uint16) for _ in range(W)]
+        cs = [oracle.compress(g, mask, k, dt) for g in grads]
+        cm = [oracle.compress_mt(g, mask, prefix, k, dt) for g in grads]
+        assert all(np.array_equal(a.view(np.uint8), b.view(np.uint8)) for a, b in zip(cs, cm))
+        r, rm = oracle.reduce_local(cs, dt), oracle.reduce_local_mt(cm, dt)
+        assert np.array_equal(r.view(np.uint8), rm.view(np.uint8))
+        d, dm = oracle.decompress(r, mask, n, dt), oracle.decompress_mt(rm, mask, prefix, n, dt)
+        assert np.array_equal(d.view(np.uint8), dm.view(np.uint8))
+    assert 1 <= oracle.mt_threads() <= 4096
