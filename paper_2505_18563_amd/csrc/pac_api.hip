@@ -122,6 +122,7 @@ void free_scratch(pac_ctx* ctx) {
     (void)hipFree(s.hist0);
     (void)hipFree(s.hist1);
     (void)hipFree(s.kept_above);
+    (void)hipFree(s.tie_count);
     (void)hipFree(s.glob);
     (void)hipFree(s.rec);
     (void)hipFree(s.match);
@@ -209,6 +210,7 @@ pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_
     alloc((void**)&s.hist0, hist0_bytes);
     alloc((void**)&s.hist1, hist1_bytes);
     alloc((void**)&s.kept_above, (size_t)max_segments * sizeof(uint32_t));
+    alloc((void**)&s.tie_count, (size_t)max_segments * sizeof(uint32_t));
     alloc((void**)&s.glob, sizeof(pac::Globals));
     alloc((void**)&s.rec, (size_t)emit_tiles * pac::kRecSlots * sizeof(unsigned long long));
     alloc((void**)&s.match, (size_t)pac::kMatchSlots * sizeof(unsigned long long));

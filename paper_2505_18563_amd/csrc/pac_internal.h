@@ -13,9 +13,12 @@ namespace pac {
 // element in three steps:
 //   bracket: a key range [lo, hi) that holds the k-th key, made of whole bins of digit 0
 //            (key bits 30..17) taken from a histogram over all, or a sample of, the scope's elements
-//   digit 1: the undecided elements (lo <= key < hi) are counted by (key - lo) >> sh1 while they
-//            are collected; the bin of the k-th among them narrows the range to 2^sh1 keys
-//   tail   : the remaining sh1 key bits and the 32 index bits, resolved inside one workgroup
+//   tie key: if one key holds a visible share of the bracket's elements (the zeros of an already pruned
+//            model, a constant tensor), its elements are not listed one by one: every tile only counts
+//            them, and their flat order decides among them at the end
+//   digit 1: the other undecided elements (lo <= key < hi) are counted by a second digit (see
+//            SegState) while they are collected; the bin of the k-th among them narrows the range
+//   tail   : the remaining key bits and the 32 index bits, resolved inside one workgroup
 constexpr uint32_t kDigit0Bits = 14;
 constexpr uint32_t kDigit0Bins = 1u << kDigit0Bits;   // 16384
 constexpr uint32_t kDigit0Shift = 17;                 // within the 31-bit key
@@ -34,21 +37,26 @@ struct SegDesc {
 };
 
 // Selection state of one prune scope, device only.
+constexpr uint32_t kNoTieKey = 0xFFFFFFFFu;   // no key is 0xFFFFFFFF (keys have 31 bits)
 struct SegState {
     unsigned long long cstar;  // composite of the k-th element: kept iff composite >= cstar
     uint32_t active;           // 0 if nothing is undecided (k == 0 or k == n): cstar is already final
     uint32_t lo;               // bracket: key >= hi is kept, lo <= key < hi is undecided
     uint32_t hi;
-    uint32_t sh1;              // digit 1 of an undecided key = (key - lo) >> sh1, below kDigit1Bins
+    uint32_t lo1;              // digit 1 of an undecided key: 0 below lo1, ((key - lo1) >> sh1) + off1 from lo1 on,
+    uint32_t sh1;              // always below kDigit1Bins; lo1 is a multiple of 2^sh1, so the keys of one digit
+    uint32_t off1;             // (other than a digit 0 below lo1) share all bits from sh1 up.  off1 = 1 iff lo1 > lo
+    uint32_t tie_key;          // kNoTieKey, or the key inside the bracket whose elements are counted per tile, not listed
+    uint32_t tie_in;           // the tie key's elements fall into digit-1 bin bin1 (cnt1 includes them)
     uint32_t exact;            // the histogram counted every element, so krem0 was known before emit
     uint32_t krem0;            // rank of the k-th element among the undecided ones (1-based, descending)
     uint32_t bin1;             // digit 1 of the k-th element
     uint32_t cnt1;             // undecided elements with that digit
     uint32_t krem1;            // rank of the k-th element among those
-    uint32_t heavy;            // too many undecided elements share digit 1 for `final`'s LDS list:
+    uint32_t heavy;            // too many listed elements share digit 1 for `final`'s LDS list:
                                // `final` walks this scope's weights
-    uint32_t pad[2];
 };
+static_assert(sizeof(SegState) == 64, "one cache line half per scope");
 
 constexpr uint32_t kMaxSampleStride = 64;  // largest SegDesc::stride (power of two)
 
@@ -58,12 +66,16 @@ constexpr uint32_t kMaxSampleStride = 64;  // largest SegDesc::stride (power of 
 constexpr uint32_t kSmallScope = 32768;
 
 // emit leaves one record per tile of kEmitTileElems elements (room for 3 % of them; a bracket of a
-// few histogram bins holds about 1 %): kRecSlots 64-bit slots, slot 0 the
-// header (elements above the bracket << 32 | listed undecided elements), then their composites.
-// A header count of kRecWalk means "not listed": consumers walk the tile's weights.
+// few histogram bins holds about 1 %): kRecSlots 64-bit slots, slot 0 the header, then the composites
+// of the listed undecided elements.  Header fields, 16 bits each from the low end:
+//   listed   undecided elements listed in the record; kRecWalk = not listed, consumers walk the tile's weights
+//   kept     elements above their bracket (used for tiles that lie inside one scope)
+//   tie_head elements equal to the tie key of the scope that holds the tile's first element
+//   tie_tail the same for the other large scope that begins inside the tile, if there is one
+// Tie-key elements are never listed and never visited by a walk: they exist as these counts only.
 constexpr uint32_t kEmitTileElems = 4096;
 constexpr uint32_t kRecSlots = 128;
-constexpr uint32_t kRecWalk = 0xFFFFFFFFu;
+constexpr uint32_t kRecWalk = 0xFFFFu;
 
 // compact2 runs with a fixed number of workgroups, each owning a short list of matches.
 constexpr uint32_t kMatchBlocks = 1024;
@@ -96,6 +108,7 @@ struct MaskScratch {
     uint32_t* hist0;               // [max_segments * kDigit0Bins], all zero between calls
     uint32_t* hist1;               // [max_segments * kDigit1Bins], all zero between calls
     uint32_t* kept_above;          // [max_segments] elements with key >= hi (counted for sampled scopes)
+    uint32_t* tie_count;           // [max_segments] elements equal to the scope's tie key
     Globals* glob;
     unsigned long long* rec;       // [tiles * kRecSlots] tile records
     uint32_t* tile_scope;          // [tiles] scope of each tile's first element (belongs to the table in `seg`)

@@ -28,6 +28,7 @@
 // not listed: count1, compact2 and fixup read that tile's weights instead.  A scope with more than
 // 4096 matches is resolved by `final` from its weights.  Same results, slower.
 #include <cstdlib>
+#include <type_traits>
 
 #include "pac_internal.h"
 
@@ -264,11 +265,12 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
 
 // ---------------------------------------------------------------------------- select0 / select1
 // Finds, in a histogram of BINS bins owned 16 per thread, the bin that holds the k-th element when
-// bins are walked from the highest digit down.  Zeroes the histogram.  Exactly one thread returns
-// true (if 1 <= k <= total count) with bin / rank-inside-bin / bin count.
+// bins are walked from the highest digit down.  `extra_cnt` further elements count in bin `extra_bin`
+// (they are not in the histogram).  Zeroes the histogram.  Exactly one thread returns true (if
+// 1 <= k <= total count) with bin / rank-inside-bin / bin count.
 template <int BINS>
-__device__ __forceinline__ bool select_bin(uint32_t* __restrict__ h, uint32_t k, uint32_t* wave_sums,
-                                           uint32_t& bin, uint32_t& krem, uint32_t& cnt) {
+__device__ __forceinline__ bool select_bin(uint32_t* __restrict__ h, uint32_t k, uint32_t extra_bin, uint32_t extra_cnt,
+                                           uint32_t* wave_sums, uint32_t& bin, uint32_t& krem, uint32_t& cnt) {
     constexpr int THREADS = BINS / 16;
     uint32_t loc[16];
     uint4* hv = reinterpret_cast<uint4*>(h) + threadIdx.x * 4;
@@ -278,6 +280,9 @@ __device__ __forceinline__ bool select_bin(uint32_t* __restrict__ h, uint32_t k,
         loc[4 * j] = x.x; loc[4 * j + 1] = x.y; loc[4 * j + 2] = x.z; loc[4 * j + 3] = x.w;
         hv[j] = make_uint4(0, 0, 0, 0);
     }
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (threadIdx.x * 16 + j == extra_bin) loc[j] += extra_cnt;
     uint32_t sum = 0;
 #pragma unroll
     for (int j = 0; j < 16; ++j) sum += loc[j];
@@ -306,41 +311,60 @@ __device__ __forceinline__ bool select_bin(uint32_t* __restrict__ h, uint32_t k,
 
 constexpr uint32_t kFinalList = 4096;   // matches of one scope that `final` can hold in LDS
 
-__device__ __forceinline__ uint32_t ceil_log2(uint32_t x) { return x <= 1 ? 0u : 32u - (uint32_t)__clz((int)(x - 1)); }
-
 // Width of the confidence band around the estimated sample rank, in standard deviations of a
 // simple random sample.  Tiles are clusters, which can inflate the variance; a bracket that misses
 // is detected after emit and the call falls back to full counts.
 constexpr double kBandSigmas = 8.0;
 
-__global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc* __restrict__ seg,
+// Digit 1 of an undecided key (see SegState).
+__device__ __forceinline__ uint32_t digit1_of(uint32_t key, uint32_t lo1, uint32_t sh1, uint32_t off1) {
+    return key < lo1 ? 0u : ((key - lo1) >> sh1) + off1;
+}
+
+// Samples of a scope that select0 looks at to find a tie key: one per thread, at hashed positions.
+constexpr uint32_t kTieVoters = 256;    // in-bracket samples that take part in the vote
+constexpr uint32_t kTieMinVotes = 8;    // a key with at least this many of them becomes the tie key
+
+__global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const float* __restrict__ w,
+                                                                   const SegDesc* __restrict__ seg,
                                                                    SegState* __restrict__ state,
                                                                    uint32_t* __restrict__ hist0,
-                                                                   uint32_t* __restrict__ kept_above, Globals* glob,
+                                                                   uint32_t* __restrict__ kept_above,
+                                                                   uint32_t* __restrict__ tie_count, Globals* glob,
                                                                    uint32_t pass) {
     constexpr int THREADS = kDigit0Bins / 16;
     __shared__ uint32_t wave_sums[THREADS / 64];
     __shared__ uint32_t sh_hi, sh_lo, sh_above_hi;
+    __shared__ uint32_t voters[kTieVoters];
+    __shared__ uint32_t n_in, n_in_tie_bin, sh_next;
+    __shared__ u64 best;
     if (pass != 0 && !glob->retry) return;
     const uint32_t s = blockIdx.x;
     const uint32_t k = seg[s].k;
-    const uint32_t n_s = seg[s].end - seg[s].begin;
+    const uint32_t begin = seg[s].begin;
+    const uint32_t n_s = seg[s].end - begin;
     SegState* st = state + s;
+    auto settle = [&](u64 cstar, uint32_t edge) {   // nothing undecided: every key is below (or at least) `edge`
+        st->cstar = cstar;
+        st->active = 0;
+        st->lo = st->hi = st->lo1 = edge;
+        st->sh1 = 0; st->off1 = 0; st->tie_key = kNoTieKey; st->tie_in = 0;
+        st->exact = 1; st->krem0 = 0; st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0; st->heavy = 0;
+    };
     if (seg[s].stride == 0) {
         // A small scope takes no part in the streaming passes: emit leaves it all-zero (no key reaches
         // hi) and its own workgroup writes its bits afterwards.  Its histogram rows stay zero.
-        if (threadIdx.x == 0) {
-            st->cstar = ~0ull;
-            st->active = 0;
-            st->lo = st->hi = kKeyEnd;
-            st->sh1 = 0; st->exact = 1; st->krem0 = 0; st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
-            st->heavy = 0;
-        }
+        if (threadIdx.x == 0) settle(~0ull, kKeyEnd);
         return;
     }
 
-    // this scope's kept counters start from zero
-    if (threadIdx.x == 0) kept_above[s] = 0;
+    // One sample of the scope per thread, for the tie-key vote further down (issued early: the histogram
+    // work below hides its latency).
+    const uint32_t sample_pos = begin + (uint32_t)(((u64)hash32(threadIdx.x * 0x9E3779B1u + s) * n_s) >> 32);
+    const uint32_t sample_key = key_of_bits(__float_as_uint(w[sample_pos]));
+
+    // this scope's counters start from zero
+    if (threadIdx.x == 0) { kept_above[s] = 0; tie_count[s] = 0; }
 
     // thread t owns bins [16t, 16t+16); read and clear them
     uint32_t loc[16];
@@ -360,14 +384,7 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
 
     if (k == 0 || k == n_s) {
         // Nothing to resolve: keep nothing (hi above every key) or everything (hi = 0).
-        const bool none = k == 0;
-        if (threadIdx.x == 0) {
-            st->cstar = none ? ~0ull : 0ull;
-            st->active = 0;
-            st->lo = st->hi = none ? kKeyEnd : 0u;
-            st->sh1 = 0; st->exact = 1; st->krem0 = 0; st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
-            st->heavy = 0;
-        }
+        if (threadIdx.x == 0) settle(k == 0 ? ~0ull : 0ull, k == 0 ? kKeyEnd : 0u);
         return;
     }
 
@@ -384,7 +401,10 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
         lo_rank = ks - kBandSigmas * sd - 2.0;
         hi_rank = ks + kBandSigmas * sd + 2.0;
     }
-    if (threadIdx.x == 0) { sh_hi = kDigit0Bins - 1; sh_lo = 0; sh_above_hi = 0; }
+    if (threadIdx.x == 0) {
+        sh_hi = kDigit0Bins - 1; sh_lo = 0; sh_above_hi = 0;
+        n_in = 0; n_in_tie_bin = 0; sh_next = kDigit0Bins; best = 0;
+    }
     __syncthreads();
     {
         // b_hi = smallest bin with (#counted above it) <= lo_rank; b_lo = largest bin with
@@ -412,13 +432,58 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const SegDesc
             cgt += loc[j];
         }
     }
+    const uint32_t lo = b_lo << kDigit0Shift;
+    const uint32_t width = ((b_hi + 1u) << kDigit0Shift) - lo;      // hi - lo, hi up to 2^31
+
+    // Tie key: the samples that fall into the bracket vote; a key that very many of them share (the zeros
+    // of a pruned model, a constant tensor) would overflow every tile's list, so its elements are only
+    // counted.  Any choice is correct - the key only decides which elements are listed and which counted.
+    const bool in_bracket = sample_key - lo < width;
+    uint32_t my_slot = kTieVoters;
+    if (in_bracket) my_slot = atomicAdd(&n_in, 1u);
+    if (my_slot < kTieVoters) voters[my_slot] = sample_key;
     __syncthreads();
+    const uint32_t n_voters = min(n_in, kTieVoters);
+    if (my_slot < kTieVoters && n_voters >= kTieMinVotes) {
+        uint32_t votes = 0;
+        for (uint32_t i = 0; i < n_voters; ++i) votes += voters[i] == sample_key ? 1u : 0u;
+        if (votes >= kTieMinVotes) atomicMax(&best, ((u64)votes << 32) | sample_key);
+    }
+    __syncthreads();
+    const bool has_tie = best != 0;
+    const uint32_t tie_key = has_tie ? (uint32_t)best : kNoTieKey;
+    // Where digit 1 starts.  If the tie key fills the lowest bin of a bracket of several bins (every sample
+    // of that bin is the tie key: the zeros below all other magnitudes), digit 1 starts at the next bin
+    // that holds anything, so that it resolves the listed elements and not the empty range above the zeros.
+    uint32_t b1_lo = b_lo;
+    if (has_tie && digit0_of(tie_key) == b_lo && b_lo < b_hi) {
+        if (digit0_of(sample_key) == b_lo && sample_key != tie_key) atomicAdd(&n_in_tie_bin, 1u);   // impure
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const uint32_t bin = threadIdx.x * 16 + j;
+            if (bin > b_lo && bin <= b_hi && loc[j] != 0) atomicMin(&sh_next, bin);
+        }
+        __syncthreads();
+        if (n_in_tie_bin == 0) b1_lo = min(sh_next, b_hi);
+    } else {
+        __syncthreads();
+    }
     if (threadIdx.x == 0) {
+        // the finest digit 1 (at least 2^6 keys per value: digit 0 already resolved the bits above) whose
+        // values stay below kDigit1Bins, with lo1 aligned to its width
+        const uint32_t off1 = b1_lo > b_lo ? 1u : 0u;
+        const u64 last_key = ((u64)(b_hi + 1u) << kDigit0Shift) - 1u;
+        uint32_t sh1 = kDigit0Shift - kDigit1Bits, lo1 = 0;
+        for (;; ++sh1) {
+            lo1 = (b1_lo << kDigit0Shift) & ~((1u << sh1) - 1u);
+            if (((last_key - lo1) >> sh1) + off1 <= kDigit1Bins - 1u) break;
+        }
         st->cstar = 0;
         st->active = 1;
-        st->lo = b_lo << kDigit0Shift;
-        st->hi = (b_hi + 1u) << kDigit0Shift;            // up to 2^31
-        st->sh1 = kDigit0Shift - kDigit1Bits + ceil_log2(b_hi - b_lo + 1u);
+        st->lo = lo;
+        st->hi = lo + width;                             // up to 2^31
+        st->lo1 = lo1; st->sh1 = sh1; st->off1 = off1;
+        st->tie_key = tie_key; st->tie_in = 0;
         st->exact = exact ? 1u : 0u;
         st->krem0 = exact ? k - sh_above_hi : 0u;
         st->bin1 = 0; st->cnt1 = 0; st->krem1 = 0;
@@ -430,6 +495,7 @@ __global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(const SegDesc
                                                                    SegState* __restrict__ state,
                                                                    uint32_t* __restrict__ hist1,
                                                                    const uint32_t* __restrict__ kept_above,
+                                                                   const uint32_t* __restrict__ tie_count,
                                                                    Globals* glob, uint32_t* __restrict__ status,
                                                                    uint32_t pass) {
     __shared__ uint32_t wave_sums[kDigit1Bins / 16 / 64];
@@ -455,15 +521,22 @@ __global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(const SegDesc
     }
     __syncthreads();
     const uint32_t rank = sh_rank;
+    // the tie key's elements were counted, not listed: they join the histogram as one lump
+    const uint32_t tie_key = active ? st->tie_key : kNoTieKey;
+    const uint32_t ties = tie_key != kNoTieKey ? tie_count[s] : 0u;
+    const uint32_t tie_bin = tie_key != kNoTieKey ? digit1_of(tie_key, st->lo1, st->sh1, st->off1) : 0xFFFFFFFFu;
     uint32_t bin = 0, krem = 0, cnt = 0;
     // (select_bin clears the histogram and finds nothing when rank is 0 or beyond the undecided count)
-    const bool mine = select_bin<(int)kDigit1Bins>(hist1 + (size_t)s * kDigit1Bins, rank, wave_sums, bin, krem, cnt);
+    const bool mine = select_bin<(int)kDigit1Bins>(hist1 + (size_t)s * kDigit1Bins, rank, tie_bin, ties, wave_sums, bin, krem, cnt);
     if (threadIdx.x == 0) sh_rank = 0;
     __syncthreads();
     if (mine) {
+        const bool tie_in = ties != 0 && bin == tie_bin;
+        const uint32_t listed = tie_in ? cnt - ties : cnt;
         st->krem0 = rank; st->bin1 = bin; st->cnt1 = cnt; st->krem1 = krem;
-        st->heavy = cnt > kFinalList ? 1u : 0u;
-        if (cnt > kFinalList) atomicOr(status, kDevSlowPath);
+        st->tie_in = tie_in ? 1u : 0u;
+        st->heavy = listed > kFinalList ? 1u : 0u;
+        if (listed > kFinalList) atomicOr(status, kDevSlowPath);
         sh_rank = 1;
     }
     __syncthreads();
@@ -498,11 +571,26 @@ constexpr uint32_t kEmitTile = kEmitWaves * kEmitWaveTile;          // 4096 elem
 constexpr uint32_t kWaveStage = 64;                                 // staged composites per wave
 static_assert(kEmitTile == kEmitTileElems, "records are per emit tile");
 
+__device__ __forceinline__ void wave_lds_sync() {
+    // Orders this wave's LDS writes before its later LDS accesses of other lanes.
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 struct EmitShared {
     u64 stage[kEmitWaves][kWaveStage];
-    uint32_t wcount[kEmitWaves];     // staged by each wave, kRecWalk if its stage overflowed
+    uint32_t wcount[kEmitWaves];     // undecided elements each wave met (more than kWaveStage: its stage overflowed)
     uint32_t wkept[kEmitWaves];
+    uint32_t wtie[kEmitWaves];       // tie-key elements: head scope in the low half, tail scope in the high half
 };
+
+__device__ __forceinline__ u64 pack_header(uint32_t listed, uint32_t kept, uint32_t tie_head, uint32_t tie_tail) {
+    return (u64)listed | ((u64)kept << 16) | ((u64)tie_head << 32) | ((u64)tie_tail << 48);
+}
+__device__ __forceinline__ uint32_t header_listed(u64 h) { return (uint32_t)h & 0xFFFFu; }
+__device__ __forceinline__ uint32_t header_kept(u64 h) { return (uint32_t)(h >> 16) & 0xFFFFu; }
+__device__ __forceinline__ uint32_t header_tie_head(u64 h) { return (uint32_t)(h >> 32) & 0xFFFFu; }
+__device__ __forceinline__ uint32_t header_tie_tail(u64 h) { return (uint32_t)(h >> 48); }
 
 // Scope of element i for a lane whose elements come in ascending order: moves (sc, sc_end) forward.
 // Returns true when the scope changed.  Requires i < n (the last scope ends at n).
@@ -517,7 +605,32 @@ __device__ __forceinline__ bool advance_scope(const SegDesc* __restrict__ seg, u
     return moved;
 }
 
-__global__ __launch_bounds__(kEmitBlock, 8) void emit_kernel(const float* __restrict__ w, uint32_t n,
+// Lane U of the pair (lo, hi) replaced by the two halves of the wave-uniform 64-bit value m: two
+// v_writelane_b32 with the lane as an immediate.  (The compiler's own lowering of `lane == U ? x : old`
+// keeps sixteen lane masks in scalar registers, which it then spills.)  m is the result of the vector
+// compare just before: the s_nop covers the "a vector instruction writes a scalar register, the next one
+// reads it: two wait states" rule of this chip, which the compiler cannot apply inside an asm statement.
+template <uint32_t U>
+__device__ __forceinline__ void set_lane_pair(u64 m, uint32_t& lo, uint32_t& hi) {
+#ifdef PAC_EMIT_CSELECT
+    lo = lane_id() == U ? (uint32_t)m : lo;
+    hi = lane_id() == U ? (uint32_t)(m >> 32) : hi;
+#else
+    asm volatile("s_nop 1\n\tv_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
+                 : "+v"(lo), "+v"(hi) : "s"((uint32_t)m), "s"((uint32_t)(m >> 32)), "n"(U));
+#endif
+}
+
+// f(std::integral_constant<uint32_t, U>) for U = 0 .. N-1, so that U is a constant where an asm operand needs one.
+template <uint32_t U, uint32_t N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (U < N) {
+        f(std::integral_constant<uint32_t, U>{});
+        static_for<U + 1, N>(f);
+    }
+}
+
+__global__ __launch_bounds__(kEmitBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void emit_kernel(const float* __restrict__ w, uint32_t n,
                                                           const SegDesc* __restrict__ seg, uint32_t nseg,
                                                           const SegState* __restrict__ state, const Globals* glob,
                                                           const uint32_t* __restrict__ tile_scope,
@@ -534,107 +647,112 @@ __global__ __launch_bounds__(kEmitBlock, 8) void emit_kernel(const float* __rest
         const u64 a = (u64)t * kEmitTile;                            // < n
         const bool whole = a + kEmitTile <= n;
         const u64 wave_first = a + wave * kEmitWaveTile;
+        // A whole tile's loads go out before anything is known about its scopes (a tile that turns out to
+        // cross a scope boundary reads its elements again, a few at a time, on the general path below).
         uint32_t v[kEmitLoads];
         if (whole) {
             const uint32_t* p = reinterpret_cast<const uint32_t*>(w) + wave_first + lane;
 #pragma unroll
             for (uint32_t u = 0; u < kEmitLoads; ++u) v[u] = __builtin_nontemporal_load(p + u * 64);
-        } else {
-#pragma unroll
-            for (uint32_t u = 0; u < kEmitLoads; ++u) {
-                const u64 i = wave_first + u * 64 + lane;
-                v[u] = i < n ? __float_as_uint(w[i]) : 0u;
-            }
         }
         const uint32_t s0 = nseg > 1 ? tile_scope[t] : 0u;
         const uint32_t s0_end = seg[s0].end;
 
-        u64 mine = 0;                 // lane u: mask word u of this wave
-        uint32_t staged = 0, kept_n = 0;
-        bool over = false;
+        // The wave's counters live in LDS: the per-element work below is vector instructions only (a
+        // compute unit issues one scalar instruction per clock for all of its waves together, and ballots
+        // that are counted step by step cost several each).  Undecided elements are rare: the few lanes
+        // that hold one append it with an LDS atomic; their order in the record does not matter.
+        if (lane == 0) { sh.wcount[wave] = 0; sh.wkept[wave] = 0; sh.wtie[wave] = 0; }
+        wave_lds_sync();
+        uint32_t mine_lo = 0, mine_hi = 0;   // lane u: mask word u of this wave
+        uint32_t my_tie = 0;                 // this lane's tie-key elements: head scope | tail scope << 16
         u64* my = sh.stage[wave];
         if (whole && (u64)s0_end >= a + kEmitTile) {
-            // the whole tile inside one scope: nothing per element but the two compares
-            const uint32_t lo = state[s0].lo, hi = state[s0].hi, width = hi - lo;
+            // the whole tile inside one scope: nothing per element but the compares
+            const uint32_t lo = state[s0].lo, hi = state[s0].hi, width = hi - lo, tie = state[s0].tie_key;
             const uint32_t i0 = (uint32_t)wave_first + lane;
-#pragma unroll
-            for (uint32_t u = 0; u < kEmitLoads; ++u) {
+            static_for<0, kEmitLoads>([&](auto uc) {
+                constexpr uint32_t u = decltype(uc)::value;
                 const uint32_t key = key_of_bits(v[u]);
                 const u64 km = __ballot(key >= hi);
-                kept_n += (uint32_t)__popcll(km);
-                if (lane == u) mine = km;
-                const bool und = key - lo < width;
-                const u64 cm = __ballot(und);
-                if (cm != 0) {
-                    const uint32_t c = (uint32_t)__popcll(cm);
-                    if (staged + c <= kWaveStage) {
-                        if (und) my[staged + lanes_below(cm)] = composite_of(key, i0 + u * 64);
-                    } else {
-                        over = true;
-                    }
-                    staged += c;
+                set_lane_pair<u>(km, mine_lo, mine_hi);
+                const bool is_tie = key == tie;                      // never true without a tie key
+                my_tie += is_tie ? 1u : 0u;
+                const uint32_t listed_key = is_tie ? 0xFFFFFFFFu : key;   // outside every bracket
+                // The accumulators take their new values here and now.  (Left to itself the compiler sinks
+                // these updates to the end of the tile and keeps sixteen steps' lane masks alive in scalar
+                // registers it does not have: they spill, and the loaded values after them.)
+                asm volatile("" : "+v"(mine_lo), "+v"(mine_hi), "+v"(my_tie));
+                if (listed_key - lo < width) {
+                    const uint32_t pos = atomicAdd(&sh.wcount[wave], 1u);
+                    if (pos < kWaveStage) my[pos] = composite_of(key, i0 + u * 64);
                 }
-            }
+            });
         } else {
             // The ragged last tile, or a tile that crosses scope boundaries: every lane follows the
             // scopes of its own (ascending) elements.  Kept counts of sampled scopes go straight to
-            // their counters (the record's count is only used for tiles inside one scope).
+            // their counters (the record's count is only used for tiles inside one scope).  At most one
+            // other large scope begins inside a tile: its tie-key elements are the header's tail count.
             const bool single = (u64)s0_end >= min(a + kEmitTile, (u64)n);
             uint32_t sc = s0, sc_end = s0_end;
-            uint32_t lo = state[s0].lo, hi = state[s0].hi, exact = state[s0].exact;
+            uint32_t lo = state[s0].lo, hi = state[s0].hi, exact = state[s0].exact, tie = state[s0].tie_key;
+            constexpr uint32_t kGroup = 4;      // loads in flight: such tiles are few, their code is kept small
+#pragma unroll 1
+            for (uint32_t u0 = 0; u0 < kEmitLoads; u0 += kGroup) {
+                uint32_t x[kGroup];
 #pragma unroll
-            for (uint32_t u = 0; u < kEmitLoads; ++u) {
-                const u64 i = wave_first + u * 64 + lane;
-                const bool valid = i < n;
-                if (valid && advance_scope(seg, (uint32_t)i, sc, sc_end)) {
-                    lo = state[sc].lo; hi = state[sc].hi; exact = state[sc].exact;
+                for (uint32_t q = 0; q < kGroup; ++q) {
+                    const u64 i = wave_first + (u0 + q) * 64 + lane;
+                    x[q] = i < n ? __float_as_uint(w[i]) : 0u;
                 }
-                const uint32_t key = key_of_bits(v[u]);
-                const bool kept = valid && key >= hi;
-                const u64 km = __ballot(kept);
-                kept_n += (uint32_t)__popcll(km);
-                if (lane == u) mine = km;
-                if (!single) wave_aggregated_inc(kept_above, sc, kept && !exact);
-                const bool und = valid && key - lo < hi - lo;
-                const u64 cm = __ballot(und);
-                if (cm != 0) {
-                    const uint32_t c = (uint32_t)__popcll(cm);
-                    if (staged + c <= kWaveStage) {
-                        if (und) my[staged + lanes_below(cm)] = composite_of(key, (uint32_t)i);
-                    } else {
-                        over = true;
+#pragma unroll
+                for (uint32_t q = 0; q < kGroup; ++q) {
+                    const uint32_t u = u0 + q;
+                    const u64 i = wave_first + u * 64 + lane;
+                    const bool valid = i < n;
+                    if (valid && advance_scope(seg, (uint32_t)i, sc, sc_end)) {
+                        lo = state[sc].lo; hi = state[sc].hi; exact = state[sc].exact; tie = state[sc].tie_key;
                     }
-                    staged += c;
+                    const uint32_t key = key_of_bits(x[q]);
+                    const bool kept = valid && key >= hi;
+                    const u64 km = __ballot(kept);
+                    mine_lo = lane == u ? (uint32_t)km : mine_lo;
+                    mine_hi = lane == u ? (uint32_t)(km >> 32) : mine_hi;
+                    if (!single) wave_aggregated_inc(kept_above, sc, kept && !exact);
+                    const bool is_tie = valid && key == tie;
+                    my_tie += is_tie ? (sc == s0 ? 1u : 0x10000u) : 0u;
+                    if (valid && !is_tie && key - lo < hi - lo) {
+                        const uint32_t pos = atomicAdd(&sh.wcount[wave], 1u);
+                        if (pos < kWaveStage) my[pos] = composite_of(key, (uint32_t)i);
+                    }
                 }
             }
         }
         if (lane < kEmitLoads) {
             const u64 wi = (wave_first >> 6) + lane;
+            const u64 mine = ((u64)mine_hi << 32) | mine_lo;
             if (wi < words) __builtin_nontemporal_store(mine, mask + wi);
+            atomicAdd(&sh.wkept[wave], (uint32_t)__popcll(mine));
         }
+        if (my_tie != 0) atomicAdd(&sh.wtie[wave], my_tie);   // two 16-bit sums side by side, each at most 1024
 
         // the tile's record: header, then the waves' entries back to back
-        if (lane == 0) {
-            sh.wcount[wave] = over ? kRecWalk : staged;
-            sh.wkept[wave] = kept_n;
-        }
         __syncthreads();
-        uint32_t off = 0, total = 0, kept_total = 0;
+        const uint32_t staged = sh.wcount[wave];
+        uint32_t off = 0, total = 0, kept_total = 0, tie_total = 0;
         bool walk = false;
 #pragma unroll
         for (int j = 0; j < kEmitWaves; ++j) {
             const uint32_t c = sh.wcount[j];
-            if (c == kRecWalk) {
-                walk = true;
-            } else {
-                if ((uint32_t)j < wave) off += c;
-                total += c;
-            }
+            if (c > kWaveStage) walk = true;      // that wave's stage overflowed
+            if ((uint32_t)j < wave) off += c;
+            total += c;
             kept_total += sh.wkept[j];
+            tie_total += sh.wtie[j];              // still two 16-bit sums, each at most 4096
         }
         if (total > rec_cap) walk = true;
         u64* r = rec + (size_t)t * kRecSlots;
-        if (threadIdx.x == 0) r[0] = ((u64)kept_total << 32) | (walk ? kRecWalk : total);
+        if (threadIdx.x == 0) r[0] = pack_header(walk ? kRecWalk : total, kept_total, tie_total & 0xFFFFu, tie_total >> 16);
         if (!walk) {
             for (uint32_t j = lane; j < staged; j += 64) r[1 + off + j] = my[j];
         }
@@ -663,12 +781,6 @@ struct WalkShared {
     uint32_t meta[64];     // tile's first scope | bit 31: the tile lies inside that scope
 };
 
-__device__ __forceinline__ void wave_lds_sync() {
-    // Orders this wave's LDS writes before its later LDS reads of other lanes' data.
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
     const uint32_t lane = lane_id();
 #pragma unroll
@@ -693,7 +805,7 @@ __device__ __forceinline__ void visit_tiles(const float* __restrict__ w, uint32_
     const uint32_t s0 = valid && nseg > 1 ? tile_scope[t] : 0u;
     const bool single = valid && (u64)seg[s0].end >= min((u64)(t + 1) * kEmitTile, (u64)n);
     if (valid) header(t, hdr, s0, single);
-    const uint32_t cnt = (uint32_t)hdr;
+    const uint32_t cnt = header_listed(hdr);
     const bool walk = valid && cnt == kRecWalk;
     const uint32_t c = valid && !walk ? cnt : 0u;
     const uint32_t incl = wave_inclusive_scan(c);
@@ -736,11 +848,11 @@ __device__ __forceinline__ void visit_tiles(const float* __restrict__ w, uint32_
         const u64 b = min(a + kEmitTile, (u64)n);
         uint32_t sc = nseg > 1 ? tile_scope[tw] : 0u;
         uint32_t sc_end = seg[sc].end;
-        uint32_t lo = state[sc].lo, hi = state[sc].hi;
+        uint32_t lo = state[sc].lo, hi = state[sc].hi, tie = state[sc].tie_key;
         for (u64 i = a + lane; i < b; i += 64) {
-            if (advance_scope(seg, (uint32_t)i, sc, sc_end)) { lo = state[sc].lo; hi = state[sc].hi; }
+            if (advance_scope(seg, (uint32_t)i, sc, sc_end)) { lo = state[sc].lo; hi = state[sc].hi; tie = state[sc].tie_key; }
             const uint32_t key = key_of_bits(__float_as_uint(w[i]));
-            if (key - lo < hi - lo) visit(composite_of(key, (uint32_t)i), sc);
+            if (key - lo < hi - lo && key != tie) visit(composite_of(key, (uint32_t)i), sc);   // tie-key elements are counted, never visited
         }
     }
 }
@@ -760,14 +872,15 @@ __global__ __launch_bounds__(kCountBlock) void count1_kernel(const float* __rest
                                                              const uint32_t* __restrict__ tile_scope,
                                                              const u64* __restrict__ rec,
                                                              uint32_t* __restrict__ hist1,
-                                                             uint32_t* __restrict__ kept_above, uint32_t pass) {
+                                                             uint32_t* __restrict__ kept_above,
+                                                             uint32_t* __restrict__ tie_count, uint32_t pass) {
     constexpr uint32_t kWaves = kCountBlock / 64;
     __shared__ uint32_t lds[kDigit1Bins];
     __shared__ WalkShared ws[kWaves];
-    __shared__ uint32_t sh_kept;
+    __shared__ uint32_t sh_kept, sh_tie;
     if (pass != 0 && !glob->retry) return;
     for (uint32_t b = threadIdx.x; b < kDigit1Bins; b += kCountBlock) lds[b] = 0;
-    if (threadIdx.x == 0) sh_kept = 0;
+    if (threadIdx.x == 0) { sh_kept = 0; sh_tie = 0; }
     __syncthreads();
     const uint32_t wave = threadIdx.x >> 6;
     const uint32_t num_tiles = (uint32_t)(((u64)n + kEmitTile - 1) / kEmitTile);
@@ -788,7 +901,9 @@ __global__ __launch_bounds__(kCountBlock) void count1_kernel(const float* __rest
         }
         if (threadIdx.x == 0) {
             if (sh_kept) atomicAdd(&kept_above[cur], sh_kept);
+            if (sh_tie) atomicAdd(&tie_count[cur], sh_tie);
             sh_kept = 0;
+            sh_tie = 0;
         }
         __syncthreads();
     };
@@ -816,16 +931,26 @@ __global__ __launch_bounds__(kCountBlock) void count1_kernel(const float* __rest
         const uint32_t t0 = t + wave * share;
         if (t0 < r_end) {
             visit_tiles(w, n, seg, nseg, state, tile_scope, rec, t0, min(r_end, t0 + share), ws[wave],
-                [&](uint32_t, u64 hdr, uint32_t s0, bool single) {
+                [&](uint32_t tile, u64 hdr, uint32_t s0, bool single) {
                     // kept elements of a tile inside one scope (emit counted the others itself)
-                    const uint32_t kept = (uint32_t)(hdr >> 32);
+                    const uint32_t kept = header_kept(hdr);
                     if (single && kept != 0 && !state[s0].exact) {
                         if (s0 == cur) atomicAdd(&sh_kept, kept);
                         else atomicAdd(&kept_above[s0], kept);
                     }
+                    // tie-key elements: of the tile's first scope, and of the large scope that begins inside it
+                    const uint32_t th = header_tie_head(hdr), tt = header_tie_tail(hdr);
+                    if (th != 0) {
+                        if (s0 == cur) atomicAdd(&sh_tie, th);
+                        else atomicAdd(&tie_count[s0], th);
+                    }
+                    if (tt != 0) {
+                        const uint32_t last = (uint32_t)(min((u64)(tile + 1) * kEmitTile, (u64)n) - 1);
+                        atomicAdd(&tie_count[find_seg(seg, nseg, last)], tt);
+                    }
                 },
                 [&](u64 c, uint32_t s) {
-                    const uint32_t d1 = ((uint32_t)(c >> 32) - state[s].lo) >> state[s].sh1;
+                    const uint32_t d1 = digit1_of((uint32_t)(c >> 32), state[s].lo1, state[s].sh1, state[s].off1);
                     if (s == cur) atomicAdd(&lds[d1], 1u);
                     else atomicAdd(&hist1[(size_t)s * kDigit1Bins + d1], 1u);
                 });
@@ -870,7 +995,8 @@ __global__ __launch_bounds__(kListBlock) void compact2_kernel(const float* __res
         visit_tiles(w, n, seg, nseg, state, tile_scope, rec, t0, t_end, ws[wave],
             [](uint32_t, u64, uint32_t, bool) {},
             [&](u64 c, uint32_t s) {
-                if (!state[s].heavy && (((uint32_t)(c >> 32) - state[s].lo) >> state[s].sh1) == state[s].bin1) {
+                if (!state[s].heavy &&
+                    digit1_of((uint32_t)(c >> 32), state[s].lo1, state[s].sh1, state[s].off1) == state[s].bin1) {
                     const uint32_t pos = atomicAdd(&nfound, 1u);
                     if (pos < kMatchSlotsPerBlock) found[pos] = c;
                 }
@@ -888,20 +1014,29 @@ __global__ __launch_bounds__(kListBlock) void compact2_kernel(const float* __res
 }
 
 // -------------------------------------------------------------------------------------- final
-// Resolves the bits of C* below digit 1 for one scope.  The source is the scope's matches, gathered
-// from the match slots into LDS (every one agrees with C* on digits 0 and 1), or, when the lists
-// are not usable, the scope's weights filtered on the fly.
+// Resolves what digits 0 and 1 left open of C* for one scope: first the remaining bits of the key, then
+// the 32 index bits.  The source is the scope's matches, gathered from the match slots into LDS (every
+// one agrees with C* on digits 0 and 1), or, when the lists are not usable, the scope's weights filtered
+// on the fly.  The tie key's elements are in no list: while key bits are resolved they count as one lump
+// at their key; if the k-th key turns out to BE the tie key, the index of the k-th element follows from
+// the tiles' tie counts in flat order (ties are kept in ascending index order) and one tile's weights.
 constexpr int kFinalBlock = 1024;
 
+// Digits of at most 8 bits, most significant first, from bit `from` of the composite down to bit `to`
+// (both multiples of... any values with from > to >= 0; a digit never straddles bit 32, where the key ends).
+// `lump` elements with composite bits `lump_c` (only its bits >= 32 matter) count besides the listed ones.
+// Read from the weights, only keys in [key_lo, key_hi) take part.
 template <bool FROM_LIST>
 __device__ __forceinline__ void final_levels(const u64* list, uint32_t list_cnt,
                                              const float* __restrict__ w, uint32_t begin, uint32_t end,
-                                             uint32_t tail_bits, u64& prefix, uint32_t& krem, uint32_t* hist,
+                                             uint32_t key_lo, uint32_t key_hi,
+                                             uint32_t from, uint32_t to, u64 lump_c, uint32_t lump,
+                                             u64& prefix, uint32_t& krem, uint32_t* hist,
                                              uint32_t* wave_sums, uint32_t* found) {
-    // 8-bit digits over the tail bits, most significant first; the last digit takes what is left
-    uint32_t resolved_above = tail_bits;   // bits >= this position are already fixed in `prefix`
-    while (resolved_above > 0) {
-        const uint32_t width = resolved_above >= 8 ? 8u : resolved_above;
+    uint32_t resolved_above = from;   // bits >= this position are already fixed in `prefix`
+    while (resolved_above > to) {
+        const uint32_t room = resolved_above > 32 && to < 32 ? resolved_above - 32 : resolved_above - to;
+        const uint32_t width = room >= 8 ? 8u : room;
         const uint32_t shift = resolved_above - width;
         if (threadIdx.x < 256) hist[threadIdx.x] = 0;
         __syncthreads();
@@ -912,11 +1047,15 @@ __device__ __forceinline__ void final_levels(const u64* list, uint32_t list_cnt,
                 c = list[j];
             } else {
                 const uint32_t i = begin + (uint32_t)j;
-                c = composite_of(key_of_bits(__float_as_uint(w[i])), i);
+                const uint32_t key = key_of_bits(__float_as_uint(w[i]));
+                if (key - key_lo >= key_hi - key_lo) continue;
+                c = composite_of(key, i);
             }
             if (((c ^ prefix) >> resolved_above) == 0)
                 atomicAdd(&hist[(uint32_t)(c >> shift) & ((1u << width) - 1u)], 1u);
         }
+        if (threadIdx.x == 0 && lump != 0 && ((lump_c ^ prefix) >> resolved_above) == 0)
+            atomicAdd(&hist[(uint32_t)(lump_c >> shift) & ((1u << width) - 1u)], lump);
         __syncthreads();
         // thread t < 256 owns bin t; walk from the highest bin down
         const uint32_t v = threadIdx.x < 256 ? hist[threadIdx.x] : 0u;
@@ -935,9 +1074,12 @@ __device__ __forceinline__ void final_levels(const u64* list, uint32_t list_cnt,
     }
 }
 
-__global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restrict__ w,
-                                                            const SegDesc* __restrict__ seg,
+__global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restrict__ w, uint32_t n,
+                                                            const SegDesc* __restrict__ seg, uint32_t nseg,
                                                             SegState* __restrict__ state, const Globals* glob,
+                                                            const uint32_t* __restrict__ tile_scope,
+                                                            const u64* __restrict__ rec,
+                                                            const uint32_t* __restrict__ tie_count,
                                                             const u64* __restrict__ match,
                                                             const uint32_t* __restrict__ match_count) {
     __shared__ u64 list[kFinalList];
@@ -945,37 +1087,100 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
     __shared__ uint32_t wave_sums[kFinalBlock / 64];
     __shared__ uint32_t found[2];
     __shared__ uint32_t gathered;
+    __shared__ uint32_t sh_tile, sh_rank, sh_index;
     const uint32_t s = blockIdx.x;
     SegState* st = state + s;
     if (!st->active) return;
-    // Every key in digit-1 bin b1 lies in [lo + (b1 << sh1), lo + ((b1 + 1) << sh1)), a range aligned
-    // to 2^sh1, so the composites there share all bits from 32 + sh1 up.
-    const uint32_t tail_bits = 32u + st->sh1;
-    u64 prefix = (u64)(st->lo + (st->bin1 << st->sh1)) << 32;
+    // The keys of digit-1 bin b1 share all bits from sh1 up (lo1 is a multiple of 2^sh1) - except for
+    // digit 0 of a digit 1 that starts above the bracket's lower end, which is just "every key below lo1".
+    const uint32_t bin1 = st->bin1, off1 = st->off1;
+    const bool below_lo1 = off1 != 0 && bin1 == 0;
+    const uint32_t key_bits = below_lo1 ? 31u : st->sh1;
+    u64 prefix = below_lo1 ? 0ull : (u64)(st->lo1 + ((bin1 - off1) << st->sh1)) << 32;
     uint32_t krem = st->krem1;
     const uint32_t begin = seg[s].begin, end = seg[s].end;
-    if (threadIdx.x == 0) { found[0] = 0; found[1] = 0; gathered = 0; }
+    if (threadIdx.x == 0) {
+        found[0] = 0; found[1] = 0; gathered = 0;
+        sh_tile = begin / kEmitTile; sh_rank = 0; sh_index = begin;   // in range whatever the counts say
+    }
     __syncthreads();
     const bool from_list = !glob->match_overflow && !st->heavy;
-    if (from_list) {
-        // Matches of this scope: thread t looks through the slots of compact2's workgroup t.
-        static_assert(kFinalBlock == (int)kMatchBlocks, "one thread per compact2 workgroup");
-        const uint32_t mine = min(match_count[threadIdx.x], kMatchSlotsPerBlock);
-        for (uint32_t e = 0; e < mine; ++e) {
-            const u64 c = match[(size_t)threadIdx.x * kMatchSlotsPerBlock + e];
-            const uint32_t i = index_of(c);
-            if (i >= begin && i < end) {
-                const uint32_t pos = atomicAdd(&gathered, 1u);
-                if (pos < kFinalList) list[pos] = c;
-            }
-        }
-        __syncthreads();
-        const uint32_t count = min(gathered, kFinalList);
-        final_levels<true>(list, count, nullptr, 0, 0, tail_bits, prefix, krem, hist, wave_sums, found);
-    } else {
-        final_levels<false>(nullptr, 0, w, begin, end, tail_bits, prefix, krem, hist, wave_sums, found);
+    const uint32_t tie_key = st->tie_key;
+    if (!from_list) {
+        // every element of the scope is read from the weights, the tie key's among them: no lump
+        final_levels<false>(nullptr, 0, w, begin, end, below_lo1 ? st->lo : 0u, below_lo1 ? st->lo1 : kKeyEnd,
+                            32u + key_bits, 0u, 0ull, 0u, prefix, krem, hist, wave_sums, found);
+        if (threadIdx.x == 0) st->cstar = prefix;
+        return;
     }
-    if (threadIdx.x == 0) st->cstar = prefix;
+    // Matches of this scope: thread t looks through the slots of compact2's workgroup t.
+    static_assert(kFinalBlock == (int)kMatchBlocks, "one thread per compact2 workgroup");
+    const uint32_t mine = min(match_count[threadIdx.x], kMatchSlotsPerBlock);
+    for (uint32_t e = 0; e < mine; ++e) {
+        const u64 c = match[(size_t)threadIdx.x * kMatchSlotsPerBlock + e];
+        const uint32_t i = index_of(c);
+        if (i >= begin && i < end) {
+            const uint32_t pos = atomicAdd(&gathered, 1u);
+            if (pos < kFinalList) list[pos] = c;
+        }
+    }
+    __syncthreads();
+    const uint32_t count = min(gathered, kFinalList);
+    const uint32_t lump = st->tie_in ? tie_count[s] : 0u;
+    const u64 lump_c = (u64)tie_key << 32;
+    final_levels<true>(list, count, nullptr, 0, 0, 0u, 0u, 32u + key_bits, 32u, lump_c, lump, prefix, krem, hist, wave_sums, found);
+    if (lump == 0 || (uint32_t)(prefix >> 32) != tie_key) {
+        // an ordinary key: the listed elements that carry it, by index
+        final_levels<true>(list, count, nullptr, 0, 0, 0u, 0u, 32u, 0u, 0ull, 0u, prefix, krem, hist, wave_sums, found);
+        if (threadIdx.x == 0) st->cstar = prefix;
+        return;
+    }
+
+    // The k-th key is the tie key: the krem-th of its elements in flat order is the last one kept.
+    // Tile counts in order: the scope's first tile may hold it as the tile's tail scope; every later tile
+    // of the scope starts inside it.
+    const uint32_t t_first = begin / kEmitTile, t_end = (end - 1u) / kEmitTile + 1u;
+    const uint32_t first_is_head = (nseg > 1 ? tile_scope[t_first] : 0u) == s ? 1u : 0u;
+    auto ties_of = [&](uint32_t t) {
+        const u64 hdr = rec[(size_t)t * kRecSlots];
+        return t == t_first && !first_is_head ? header_tie_tail(hdr) : header_tie_head(hdr);
+    };
+    const uint32_t per = (t_end - t_first + kFinalBlock - 1) / kFinalBlock;
+    const uint32_t my_first = min(t_end, t_first + threadIdx.x * per), my_end = min(t_end, my_first + per);
+    uint32_t my_sum = 0;
+    for (uint32_t t = my_first; t < my_end; ++t) my_sum += ties_of(t);
+    uint32_t total;
+    const uint32_t before = block_exclusive_scan<kFinalBlock>(my_sum, wave_sums, total);
+    if (before < krem && krem <= before + my_sum) {
+        uint32_t acc = before;
+        for (uint32_t t = my_first; t < my_end; ++t) {
+            const uint32_t c = ties_of(t);
+            if (krem <= acc + c) { sh_tile = t; sh_rank = krem - acc; break; }
+            acc += c;
+        }
+    }
+    __syncthreads();
+    // that tile's part of the scope, four consecutive elements per thread: the sh_rank-th tie-key element
+    const uint32_t tile = sh_tile, want = sh_rank;
+    const u64 ta = max((u64)tile * kEmitTile, (u64)begin), tb = min((u64)(tile + 1) * kEmitTile, (u64)end);
+    uint32_t hits[4], mine_n = 0;
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+        const u64 i = (u64)tile * kEmitTile + threadIdx.x * 4u + q;
+        hits[q] = i >= ta && i < tb && key_of_bits(__float_as_uint(w[i])) == tie_key ? 1u : 0u;
+        mine_n += hits[q];
+    }
+    const uint32_t ahead = block_exclusive_scan<kFinalBlock>(mine_n, wave_sums, total);
+    if (ahead < want && want <= ahead + mine_n) {
+        uint32_t acc = ahead;
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            acc += hits[q];
+            if (hits[q] && acc == want) sh_index = tile * kEmitTile + threadIdx.x * 4u + q;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) st->cstar = composite_of(tie_key, sh_index);
 }
 
 // -------------------------------------------------------------------------------- small scopes
@@ -1107,7 +1312,10 @@ __global__ __launch_bounds__(kSmallBlock) void small_scope_kernel(const float* _
 }
 
 // -------------------------------------------------------------------------------------- fixup
-// Undecided elements at or above their scope's C* are kept: set their mask bits.
+// Undecided elements at or above their scope's C* are kept: set their mask bits.  Listed elements (and
+// those of walked tiles) one by one; the tie key's elements, which no list holds, by reading again the
+// tiles in which some of them are kept - none if the k-th key lies above the tie key (the zeros of a
+// pruned model), the tiles up to the one that holds the k-th element if it is the tie key itself.
 __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restrict__ w, uint32_t n,
                                                            const SegDesc* __restrict__ seg, uint32_t nseg,
                                                            const SegState* __restrict__ state,
@@ -1118,19 +1326,61 @@ __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restri
     // The scan that follows starts from cleared tile states.
     for (u64 j = (u64)blockIdx.x * kListBlock + threadIdx.x; j < scan_tiles; j += (u64)gridDim.x * kListBlock)
         tile_state[j] = 0;
+    const uint32_t lane = lane_id();
     const uint32_t wave = threadIdx.x >> 6;
     const uint32_t num_tiles = (uint32_t)(((u64)n + kEmitTile - 1) / kEmitTile);
     uint32_t t_begin, t_end;
     wave_tile_range(num_tiles, blockIdx.x * (kListBlock / 64) + wave, t_begin, t_end);
     for (uint32_t t0 = t_begin; t0 < t_end; t0 += 64) {
+        bool reread = false;      // this lane's tile holds tie-key elements that are kept
         visit_tiles(w, n, seg, nseg, state, tile_scope, rec, t0, t_end, ws[wave],
-            [](uint32_t, u64, uint32_t, bool) {},
+            [&](uint32_t tile, u64 hdr, uint32_t s0, bool) {
+                // The first element of a part has the largest composite its tie-key elements can have.
+                if (header_tie_head(hdr) != 0 && state[s0].tie_key != kNoTieKey &&
+                    composite_of(state[s0].tie_key, tile * kEmitTile) >= state[s0].cstar)
+                    reread = true;
+                if (header_tie_tail(hdr) != 0) {
+                    const uint32_t last = (uint32_t)(min((u64)(tile + 1) * kEmitTile, (u64)n) - 1);
+                    const uint32_t s1 = find_seg(seg, nseg, last);
+                    if (state[s1].tie_key != kNoTieKey && composite_of(state[s1].tie_key, seg[s1].begin) >= state[s1].cstar)
+                        reread = true;
+                }
+            },
             [&](u64 c, uint32_t s) {
                 if (c >= state[s].cstar) {
                     const uint32_t i = index_of(c);
                     atomicOr(&mask[i >> 6], 1ull << (i & 63u));
                 }
             });
+        u64 todo = __ballot(reread);
+        while (todo != 0) {
+            const uint32_t j = (uint32_t)__ffsll((long long)todo) - 1u;
+            todo &= todo - 1;
+            const uint32_t tw = t0 + j;
+            const u64 a = (u64)tw * kEmitTile;
+            uint32_t sc = nseg > 1 ? tile_scope[tw] : 0u;
+            uint32_t sc_end = seg[sc].end;
+            uint32_t tie = state[sc].tie_key;
+            u64 cstar = state[sc].cstar;
+            // 64 rows of 64 elements, one mask word per row; 16 rows' loads in flight
+            for (uint32_t r0 = 0; r0 < kEmitTile / 64; r0 += 16) {
+                uint32_t v[16];
+#pragma unroll
+                for (uint32_t q = 0; q < 16; ++q) {
+                    const u64 i = a + (u64)(r0 + q) * 64 + lane;
+                    v[q] = i < n ? __float_as_uint(w[i]) : 0u;
+                }
+#pragma unroll
+                for (uint32_t q = 0; q < 16; ++q) {
+                    const u64 i = a + (u64)(r0 + q) * 64 + lane;
+                    const bool valid = i < n;
+                    if (valid && advance_scope(seg, (uint32_t)i, sc, sc_end)) { tie = state[sc].tie_key; cstar = state[sc].cstar; }
+                    const uint32_t key = key_of_bits(v[q]);
+                    const u64 bits = __ballot(valid && key == tie && composite_of(key, (uint32_t)i) >= cstar);
+                    if (bits != 0 && lane == 0) atomicOr(&mask[(a >> 6) + r0 + q], bits);
+                }
+            }
+        }
     }
 }
 
@@ -1362,8 +1612,8 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
         else
             hipLaunchKernelGGL((hist0_kernel<false>), dim3(grid), dim3(kHistBlock), 0, stream, d_weights, n,
                                s.seg, nseg, s.hist0, s.glob, pass);
-        hipLaunchKernelGGL(select0_kernel, dim3(nseg), dim3(kDigit0Bins / 16), 0, stream, s.seg, s.state, s.hist0,
-                           s.kept_above, s.glob, pass);
+        hipLaunchKernelGGL(select0_kernel, dim3(nseg), dim3(kDigit0Bins / 16), 0, stream, d_weights, s.seg, s.state,
+                           s.hist0, s.kept_above, s.tie_count, s.glob, pass);
         // One workgroup per tile; the retry pass, which almost never runs, strides over the tiles
         // with a small grid so that its launch costs little.
         const uint32_t emit_grid = pass == 0 || emit_tiles < 2048 ? emit_tiles : 2048u;
@@ -1386,15 +1636,15 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
         }
         const uint32_t count_grid = emit_tiles < kCountBlocks ? emit_tiles : kCountBlocks;
         hipLaunchKernelGGL(count1_kernel, dim3(count_grid), dim3(kCountBlock), 0, stream, d_weights, n, s.seg, nseg,
-                           s.state, s.glob, s.tile_scope, s.rec, s.hist1, s.kept_above, pass);
+                           s.state, s.glob, s.tile_scope, s.rec, s.hist1, s.kept_above, s.tie_count, pass);
         hipLaunchKernelGGL(select1_kernel, dim3(nseg), dim3(kDigit1Bins / 16), 0, stream, s.seg, s.state, s.hist1,
-                           s.kept_above, s.glob, s.status, pass);
+                           s.kept_above, s.tie_count, s.glob, s.status, pass);
     }
 
     hipLaunchKernelGGL(compact2_kernel, dim3(kMatchBlocks), dim3(kListBlock), 0, stream, d_weights, n, s.seg, nseg,
                        s.state, s.glob, s.tile_scope, s.rec, s.match, s.match_count, s.status);
-    hipLaunchKernelGGL(final_kernel, dim3(nseg), dim3(kFinalBlock), 0, stream, d_weights, s.seg, s.state, s.glob,
-                       s.match, s.match_count);
+    hipLaunchKernelGGL(final_kernel, dim3(nseg), dim3(kFinalBlock), 0, stream, d_weights, n, s.seg, nseg, s.state,
+                       s.glob, s.tile_scope, s.rec, s.tie_count, s.match, s.match_count);
     const uint32_t scan_tiles = scan_tiles_for(words);
     hipLaunchKernelGGL(fixup_kernel, dim3(kMatchBlocks), dim3(kListBlock), 0, stream, d_weights, n, s.seg, nseg,
                        s.state, s.tile_scope, s.rec, d_mask, s.tile_state, scan_tiles);
