@@ -125,6 +125,7 @@ void free_scratch(pac_ctx* ctx) {
     (void)hipFree(s.tie_count);
     (void)hipFree(s.glob);
     (void)hipFree(s.rec);
+    (void)hipFree(s.hdrs);
     (void)hipFree(s.match);
     (void)hipFree(s.match_count);
     (void)hipFree(s.tile_state);
@@ -213,6 +214,7 @@ pac_status pac_create(pac_ctx** out, int hip_device, uint64_t max_elems, uint32_
     alloc((void**)&s.tie_count, (size_t)max_segments * sizeof(uint32_t));
     alloc((void**)&s.glob, sizeof(pac::Globals));
     alloc((void**)&s.rec, (size_t)emit_tiles * pac::kRecSlots * sizeof(unsigned long long));
+    alloc((void**)&s.hdrs, (size_t)emit_tiles * sizeof(unsigned long long));
     alloc((void**)&s.match, (size_t)pac::kMatchSlots * sizeof(unsigned long long));
     alloc((void**)&s.match_count, (size_t)pac::kMatchBlocks * sizeof(uint32_t));
     alloc((void**)&s.tile_state, (size_t)(pac::kScanMaxTiles + 1) * sizeof(unsigned long long));

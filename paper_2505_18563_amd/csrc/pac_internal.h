@@ -65,9 +65,10 @@ constexpr uint32_t kMaxSampleStride = 64;  // largest SegDesc::stride (power of 
 // the streaming passes.
 constexpr uint32_t kSmallScope = 32768;
 
-// emit leaves one record per tile of kEmitTileElems elements (room for 3 % of them; a bracket of a
-// few histogram bins holds about 1 %): kRecSlots 64-bit slots, slot 0 the header, then the composites
-// of the listed undecided elements.  Header fields, 16 bits each from the low end:
+// emit leaves one record per tile of kEmitTileElems elements: a 64-bit header (in an array of its own, so
+// that the passes that only need headers read them densely) and up to kRecSlots composites of listed
+// undecided elements (room for 3 % of the tile; a sampled bracket holds a few tenths of a percent).
+// Header fields, 16 bits each from the low end:
 //   listed   undecided elements listed in the record; kRecWalk = not listed, consumers walk the tile's weights
 //   kept     elements above their bracket (used for tiles that lie inside one scope)
 //   tie_head elements equal to the tie key of the scope that holds the tile's first element
@@ -110,7 +111,8 @@ struct MaskScratch {
     uint32_t* kept_above;          // [max_segments] elements with key >= hi (counted for sampled scopes)
     uint32_t* tie_count;           // [max_segments] elements equal to the scope's tie key
     Globals* glob;
-    unsigned long long* rec;       // [tiles * kRecSlots] tile records
+    unsigned long long* hdrs;      // [tiles] tile record headers
+    unsigned long long* rec;       // [tiles * kRecSlots] tile records: the listed composites
     uint32_t* tile_scope;          // [tiles] scope of each tile's first element (belongs to the table in `seg`)
     unsigned long long* match;     // [kMatchSlots] undecided elements whose digit 1 is their scope's bin1 as
                                    // well, kMatchSlotsPerBlock slots per workgroup of compact2

@@ -80,6 +80,19 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
     return v;
 }
 
+// Sum of v over the 64 lanes, the same in every lane's return value; all lanes must be active.  Four
+// cross-lane adds inside each row of 16 lanes, then the four row sums through scalar registers.  (An LDS
+// atomic add of 64 different values to one address is turned by the compiler into a scalar loop over the
+// lanes, seven scalar instructions each.)
+__device__ __forceinline__ uint32_t wave_sum_rows(uint32_t v) {
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true);   // row_half_mirror
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true);   // row_mirror
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 0) + (uint32_t)__builtin_amdgcn_readlane((int)v, 16) +
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 32) + (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+}
+
 // atomicAdd(base + idx, 1) for every lane with `active`.  Equal magnitudes (all-zero biases, unit
 // norm scales) put whole waves on one counter, and atomics on one address are serialised: when all
 // active lanes agree on idx the wave issues a single atomic with their number; otherwise the lanes
@@ -136,6 +149,19 @@ constexpr int kHistBlock = 1024;
 constexpr uint32_t kHistLoads = 4;                                 // 16-byte loads per thread per tile
 constexpr uint32_t kHistTile = kHistBlock * 4 * kHistLoads;        // 16384 elements
 
+// ++lds[d] for every lane with `active`.  LDS atomics on one address are serialised lane by lane, and a
+// tensor with very many equal magnitudes (the zeros of a pruned model) sends most lanes of every wave to
+// one bin: the lanes that share the first active lane's bin go in as one add of their number.
+__device__ __forceinline__ void count_digit0(uint32_t* lds, uint32_t d, bool active) {
+    const u64 todo = __ballot(active);
+    if (todo == 0) return;
+    const uint32_t leader = (uint32_t)__ffsll((long long)todo) - 1u;
+    const uint32_t d_lead = (uint32_t)__builtin_amdgcn_readlane((int)d, (int)leader);
+    const u64 same = __ballot(active && d == d_lead);
+    if (active && d != d_lead) atomicAdd(&lds[d], 1u);
+    else if (lane_id() == leader) atomicAdd(&lds[d_lead], (uint32_t)__popcll(same));
+}
+
 __device__ __forceinline__ void flush_hist0(uint32_t* lds, uint32_t* __restrict__ global_hist) {
     __syncthreads();
     for (uint32_t b = threadIdx.x; b < kDigit0Bins; b += kHistBlock) {
@@ -159,7 +185,7 @@ __device__ __forceinline__ void hist0_range(const float* __restrict__ w, u64 fro
         for (uint32_t q = 0; q < kFlight; ++q) v[q] = __float_as_uint(w[min(i0 + q * kHistBlock, to - 1)]);
 #pragma unroll
         for (uint32_t q = 0; q < kFlight; ++q)
-            if (i0 + q * kHistBlock < to) atomicAdd(&lds[digit0_of(key_of_bits(v[q]))], 1u);
+            count_digit0(lds, digit0_of(key_of_bits(v[q])), i0 + q * kHistBlock < to);
     }
 }
 
@@ -228,10 +254,10 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
                 for (uint32_t u = 0; u < kHistLoads; ++u) v[u] = __builtin_nontemporal_load(p + u * kHistBlock);
 #pragma unroll
                 for (uint32_t u = 0; u < kHistLoads; ++u) {
-                    atomicAdd(&lds[digit0_of(key_of_bits(v[u].x))], 1u);
-                    atomicAdd(&lds[digit0_of(key_of_bits(v[u].y))], 1u);
-                    atomicAdd(&lds[digit0_of(key_of_bits(v[u].z))], 1u);
-                    atomicAdd(&lds[digit0_of(key_of_bits(v[u].w))], 1u);
+                    count_digit0(lds, digit0_of(key_of_bits(v[u].x)), true);
+                    count_digit0(lds, digit0_of(key_of_bits(v[u].y)), true);
+                    count_digit0(lds, digit0_of(key_of_bits(v[u].z)), true);
+                    count_digit0(lds, digit0_of(key_of_bits(v[u].w)), true);
                 }
             } else {
                 hist0_range(w, a, b, lds);
@@ -334,7 +360,7 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const float* 
                                                                    uint32_t pass) {
     constexpr int THREADS = kDigit0Bins / 16;
     __shared__ uint32_t wave_sums[THREADS / 64];
-    __shared__ uint32_t sh_hi, sh_lo, sh_above_hi;
+    __shared__ uint32_t sh_hi, sh_lo, sh_above_hi, sh_lo_key, sh_hi_cut;
     __shared__ uint32_t voters[kTieVoters];
     __shared__ uint32_t n_in, n_in_tie_bin, sh_next;
     __shared__ u64 best;
@@ -366,20 +392,24 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const float* 
     // this scope's counters start from zero
     if (threadIdx.x == 0) { kept_above[s] = 0; tie_count[s] = 0; }
 
-    // thread t owns bins [16t, 16t+16); read and clear them
+    // thread t owns bins [16t, 16t+16); read them (and the two bins next to them), then clear them
     uint32_t loc[16];
-    uint4* hv = reinterpret_cast<uint4*>(hist0 + (size_t)s * kDigit0Bins) + threadIdx.x * 4;
+    uint32_t* row = hist0 + (size_t)s * kDigit0Bins;
+    uint4* hv = reinterpret_cast<uint4*>(row) + threadIdx.x * 4;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint4 x = hv[j];
         loc[4 * j] = x.x; loc[4 * j + 1] = x.y; loc[4 * j + 2] = x.z; loc[4 * j + 3] = x.w;
-        hv[j] = make_uint4(0, 0, 0, 0);
     }
+    const uint32_t bin_before = threadIdx.x > 0 ? row[threadIdx.x * 16 - 1] : 0u;
+    const uint32_t bin_after = threadIdx.x + 1 < THREADS ? row[threadIdx.x * 16 + 16] : 0u;
     uint32_t sum = 0;
 #pragma unroll
     for (int j = 0; j < 16; ++j) sum += loc[j];
     uint32_t counted;   // elements the histogram pass visited
-    const uint32_t below = block_exclusive_scan<THREADS>(sum, wave_sums, counted);
+    const uint32_t below = block_exclusive_scan<THREADS>(sum, wave_sums, counted);   // (barriers: every read above is done)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) hv[j] = make_uint4(0, 0, 0, 0);
     const uint32_t above = counted - below - sum;   // elements in bins owned by higher threads
 
     if (k == 0 || k == n_s) {
@@ -425,15 +455,47 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const float* 
     const uint32_t b_hi = sh_hi;
     const uint32_t b_lo = min(sh_lo, b_hi);
     {
+        // A sampled bracket need not end on bin boundaries (emit counts what lies above it, select1 checks
+        // that it held the k-th key): inside its two end bins the ends move to where the rank band ends,
+        // taking the keys of a bin as evenly spread - if the bin is well filled and both bins next to it
+        // hold comparable numbers (a bin that stands alone is a lump of equal values, like the zeros of a
+        // pruned model, and is taken whole).  Where the guess is wrong the check fails and the call falls
+        // back to full counts and whole bins.
+        constexpr uint32_t kBinKeys = 1u << kDigit0Shift;
+        constexpr uint32_t kMinForCut = 64;      // sampled elements in a bin before its inside is trusted
         uint32_t cgt = above;
 #pragma unroll
         for (int j = 15; j >= 0; --j) {
-            if (threadIdx.x * 16 + j == b_hi) sh_above_hi = cgt;
-            cgt += loc[j];
+            const uint32_t bin = threadIdx.x * 16 + j, c = loc[j];
+            const uint32_t left = j > 0 ? loc[j > 0 ? j - 1 : 0] : bin_before;
+            const uint32_t right = j < 15 ? loc[j < 15 ? j + 1 : 15] : bin_after;
+            const bool smooth = c >= kMinForCut && left >= c / 4 && right >= c / 4;
+            if (bin == b_hi) {
+                sh_above_hi = cgt;
+                uint32_t cut = 0;                // keys taken off the top of bin b_hi (they count as kept)
+                if (!exact && smooth) {
+                    const double f = (lo_rank - (double)cgt) / (double)c;
+                    if (f > 0.0) cut = (uint32_t)fmin(f * (double)kBinKeys, (double)(kBinKeys - 1u));
+                }
+                sh_hi_cut = cut;
+            }
+            if (bin == b_lo) {
+                uint32_t lo_key = bin << kDigit0Shift;
+                if (!exact && smooth) {
+                    const double f = ((hi_rank - (double)cgt) / (double)c) * (double)kBinKeys;
+                    if (f < (double)kBinKeys) lo_key += kBinKeys - (uint32_t)ceil(fmax(f, 1.0));
+                }
+                sh_lo_key = lo_key;
+            }
+            cgt += c;
         }
     }
-    const uint32_t lo = b_lo << kDigit0Shift;
-    const uint32_t width = ((b_hi + 1u) << kDigit0Shift) - lo;      // hi - lo, hi up to 2^31
+    __syncthreads();
+    // (two ends in one bin: the band is at least a few elements wide, so lo stays below hi; an empty
+    // bracket would simply fail select1's check)
+    const u64 hi_key = ((u64)(b_hi + 1u) << kDigit0Shift) - sh_hi_cut;       // up to 2^31
+    const uint32_t lo = (u64)sh_lo_key < hi_key ? sh_lo_key : (uint32_t)hi_key;
+    const uint32_t width = (uint32_t)(hi_key - lo);
 
     // Tie key: the samples that fall into the bracket vote; a key that very many of them share (the zeros
     // of a pruned model, a constant tensor) would overflow every tile's list, so its elements are only
@@ -469,14 +531,14 @@ __global__ __launch_bounds__(kDigit0Bins / 16) void select0_kernel(const float* 
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        // the finest digit 1 (at least 2^6 keys per value: digit 0 already resolved the bits above) whose
-        // values stay below kDigit1Bins, with lo1 aligned to its width
+        // the finest digit 1 whose values stay below kDigit1Bins, with lo1 aligned to its width
         const uint32_t off1 = b1_lo > b_lo ? 1u : 0u;
-        const u64 last_key = ((u64)(b_hi + 1u) << kDigit0Shift) - 1u;
-        uint32_t sh1 = kDigit0Shift - kDigit1Bits, lo1 = 0;
+        const uint32_t first_key = off1 ? b1_lo << kDigit0Shift : lo;
+        const u64 last_key = hi_key - 1u;
+        uint32_t sh1 = 0, lo1 = 0;
         for (;; ++sh1) {
-            lo1 = (b1_lo << kDigit0Shift) & ~((1u << sh1) - 1u);
-            if (((last_key - lo1) >> sh1) + off1 <= kDigit1Bins - 1u) break;
+            lo1 = first_key & ~((1u << sh1) - 1u);
+            if (last_key < lo1 || ((last_key - lo1) >> sh1) + off1 <= kDigit1Bins - 1u) break;
         }
         st->cstar = 0;
         st->active = 1;
@@ -634,8 +696,9 @@ __global__ __launch_bounds__(kEmitBlock) __attribute__((amdgpu_waves_per_eu(8, 8
                                                           const SegDesc* __restrict__ seg, uint32_t nseg,
                                                           const SegState* __restrict__ state, const Globals* glob,
                                                           const uint32_t* __restrict__ tile_scope,
-                                                          uint32_t* __restrict__ kept_above, u64* __restrict__ rec,
-                                                          uint32_t rec_cap, u64* __restrict__ mask, uint32_t pass) {
+                                                          uint32_t* __restrict__ kept_above, u64* __restrict__ hdrs,
+                                                          u64* __restrict__ rec, uint32_t rec_cap,
+                                                          u64* __restrict__ mask, uint32_t pass) {
     __shared__ EmitShared sh;
     if (pass != 0 && !glob->retry) return;             // the retry pass has nothing to do
     const uint32_t lane = lane_id();
@@ -662,7 +725,7 @@ __global__ __launch_bounds__(kEmitBlock) __attribute__((amdgpu_waves_per_eu(8, 8
         // compute unit issues one scalar instruction per clock for all of its waves together, and ballots
         // that are counted step by step cost several each).  Undecided elements are rare: the few lanes
         // that hold one append it with an LDS atomic; their order in the record does not matter.
-        if (lane == 0) { sh.wcount[wave] = 0; sh.wkept[wave] = 0; sh.wtie[wave] = 0; }
+        if (lane == 0) sh.wcount[wave] = 0;
         wave_lds_sync();
         uint32_t mine_lo = 0, mine_hi = 0;   // lane u: mask word u of this wave
         uint32_t my_tie = 0;                 // this lane's tie-key elements: head scope | tail scope << 16
@@ -728,13 +791,14 @@ __global__ __launch_bounds__(kEmitBlock) __attribute__((amdgpu_waves_per_eu(8, 8
                 }
             }
         }
+        const u64 mine = ((u64)mine_hi << 32) | mine_lo;     // lanes 0..15; zero in the others
         if (lane < kEmitLoads) {
             const u64 wi = (wave_first >> 6) + lane;
-            const u64 mine = ((u64)mine_hi << 32) | mine_lo;
             if (wi < words) __builtin_nontemporal_store(mine, mask + wi);
-            atomicAdd(&sh.wkept[wave], (uint32_t)__popcll(mine));
         }
-        if (my_tie != 0) atomicAdd(&sh.wtie[wave], my_tie);   // two 16-bit sums side by side, each at most 1024
+        const uint32_t kept_n = wave_sum_rows((uint32_t)__popcll(mine));
+        const uint32_t tie_n = wave_sum_rows(my_tie);         // two 16-bit sums side by side, each at most 1024
+        if (lane == 0) { sh.wkept[wave] = kept_n; sh.wtie[wave] = tie_n; }
 
         // the tile's record: header, then the waves' entries back to back
         __syncthreads();
@@ -752,9 +816,9 @@ __global__ __launch_bounds__(kEmitBlock) __attribute__((amdgpu_waves_per_eu(8, 8
         }
         if (total > rec_cap) walk = true;
         u64* r = rec + (size_t)t * kRecSlots;
-        if (threadIdx.x == 0) r[0] = pack_header(walk ? kRecWalk : total, kept_total, tie_total & 0xFFFFu, tie_total >> 16);
+        if (threadIdx.x == 0) hdrs[t] = pack_header(walk ? kRecWalk : total, kept_total, tie_total & 0xFFFFu, tie_total >> 16);
         if (!walk) {
-            for (uint32_t j = lane; j < staged; j += 64) r[1 + off + j] = my[j];
+            for (uint32_t j = lane; j < staged; j += 64) r[off + j] = my[j];
         }
         t += gridDim.x;
         if (t >= num_tiles) break;
@@ -795,13 +859,14 @@ template <typename Header, typename Visit>
 __device__ __forceinline__ void visit_tiles(const float* __restrict__ w, uint32_t n,
                                             const SegDesc* __restrict__ seg, uint32_t nseg,
                                             const SegState* __restrict__ state,
-                                            const uint32_t* __restrict__ tile_scope, const u64* __restrict__ rec,
+                                            const uint32_t* __restrict__ tile_scope, const u64* __restrict__ hdrs,
+                                            const u64* __restrict__ rec,
                                             uint32_t t0, uint32_t t_end, WalkShared& ws, Header header,
                                             Visit visit) {
     const uint32_t lane = lane_id();
     const uint32_t t = t0 + lane;
     const bool valid = t < t_end;
-    const u64 hdr = valid ? rec[(size_t)t * kRecSlots] : 0ull;
+    const u64 hdr = valid ? hdrs[t] : 0ull;
     const uint32_t s0 = valid && nseg > 1 ? tile_scope[t] : 0u;
     const bool single = valid && (u64)seg[s0].end >= min((u64)(t + 1) * kEmitTile, (u64)n);
     if (valid) header(t, hdr, s0, single);
@@ -828,7 +893,7 @@ __device__ __forceinline__ void visit_tiles(const float* __restrict__ w, uint32_
 #pragma unroll
                 for (uint32_t step = 32; step >= 1; step >>= 1)
                     if (ws.excl[j + step] <= e) j += step;   // j + step <= 63
-                cmp[q] = rec[(size_t)(t0 + j) * kRecSlots + 1 + (e - ws.excl[j])];
+                cmp[q] = rec[(size_t)(t0 + j) * kRecSlots + (e - ws.excl[j])];
                 m[q] = ws.meta[j];
             }
         }
@@ -870,7 +935,7 @@ __global__ __launch_bounds__(kCountBlock) void count1_kernel(const float* __rest
                                                              const SegDesc* __restrict__ seg, uint32_t nseg,
                                                              const SegState* __restrict__ state, const Globals* glob,
                                                              const uint32_t* __restrict__ tile_scope,
-                                                             const u64* __restrict__ rec,
+                                                             const u64* __restrict__ hdrs, const u64* __restrict__ rec,
                                                              uint32_t* __restrict__ hist1,
                                                              uint32_t* __restrict__ kept_above,
                                                              uint32_t* __restrict__ tie_count, uint32_t pass) {
@@ -930,7 +995,7 @@ __global__ __launch_bounds__(kCountBlock) void count1_kernel(const float* __rest
         const uint32_t share = (r_end - t + kWaves - 1) / kWaves;
         const uint32_t t0 = t + wave * share;
         if (t0 < r_end) {
-            visit_tiles(w, n, seg, nseg, state, tile_scope, rec, t0, min(r_end, t0 + share), ws[wave],
+            visit_tiles(w, n, seg, nseg, state, tile_scope, hdrs, rec, t0, min(r_end, t0 + share), ws[wave],
                 [&](uint32_t tile, u64 hdr, uint32_t s0, bool single) {
                     // kept elements of a tile inside one scope (emit counted the others itself)
                     const uint32_t kept = header_kept(hdr);
@@ -979,7 +1044,8 @@ __global__ __launch_bounds__(kListBlock) void compact2_kernel(const float* __res
                                                               const SegDesc* __restrict__ seg, uint32_t nseg,
                                                               const SegState* __restrict__ state, Globals* glob,
                                                               const uint32_t* __restrict__ tile_scope,
-                                                              const u64* __restrict__ rec, u64* __restrict__ match,
+                                                              const u64* __restrict__ hdrs, const u64* __restrict__ rec,
+                                                              u64* __restrict__ match,
                                                               uint32_t* __restrict__ match_count,
                                                               uint32_t* __restrict__ status) {
     __shared__ u64 found[kMatchSlotsPerBlock];
@@ -992,7 +1058,7 @@ __global__ __launch_bounds__(kListBlock) void compact2_kernel(const float* __res
     uint32_t t_begin, t_end;
     wave_tile_range(num_tiles, blockIdx.x * (kListBlock / 64) + wave, t_begin, t_end);
     for (uint32_t t0 = t_begin; t0 < t_end; t0 += 64) {
-        visit_tiles(w, n, seg, nseg, state, tile_scope, rec, t0, t_end, ws[wave],
+        visit_tiles(w, n, seg, nseg, state, tile_scope, hdrs, rec, t0, t_end, ws[wave],
             [](uint32_t, u64, uint32_t, bool) {},
             [&](u64 c, uint32_t s) {
                 if (!state[s].heavy &&
@@ -1078,7 +1144,7 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
                                                             const SegDesc* __restrict__ seg, uint32_t nseg,
                                                             SegState* __restrict__ state, const Globals* glob,
                                                             const uint32_t* __restrict__ tile_scope,
-                                                            const u64* __restrict__ rec,
+                                                            const u64* __restrict__ hdrs,
                                                             const uint32_t* __restrict__ tie_count,
                                                             const u64* __restrict__ match,
                                                             const uint32_t* __restrict__ match_count) {
@@ -1108,7 +1174,8 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
     const uint32_t tie_key = st->tie_key;
     if (!from_list) {
         // every element of the scope is read from the weights, the tie key's among them: no lump
-        final_levels<false>(nullptr, 0, w, begin, end, below_lo1 ? st->lo : 0u, below_lo1 ? st->lo1 : kKeyEnd,
+        // (only undecided keys take part: a digit-1 bin may reach beyond the bracket's upper end)
+        final_levels<false>(nullptr, 0, w, begin, end, st->lo, below_lo1 ? st->lo1 : st->hi,
                             32u + key_bits, 0u, 0ull, 0u, prefix, krem, hist, wave_sums, found);
         if (threadIdx.x == 0) st->cstar = prefix;
         return;
@@ -1142,13 +1209,19 @@ __global__ __launch_bounds__(kFinalBlock) void final_kernel(const float* __restr
     const uint32_t t_first = begin / kEmitTile, t_end = (end - 1u) / kEmitTile + 1u;
     const uint32_t first_is_head = (nseg > 1 ? tile_scope[t_first] : 0u) == s ? 1u : 0u;
     auto ties_of = [&](uint32_t t) {
-        const u64 hdr = rec[(size_t)t * kRecSlots];
+        const u64 hdr = hdrs[t];
         return t == t_first && !first_is_head ? header_tie_tail(hdr) : header_tie_head(hdr);
     };
     const uint32_t per = (t_end - t_first + kFinalBlock - 1) / kFinalBlock;
     const uint32_t my_first = min(t_end, t_first + threadIdx.x * per), my_end = min(t_end, my_first + per);
     uint32_t my_sum = 0;
-    for (uint32_t t = my_first; t < my_end; ++t) my_sum += ties_of(t);
+    for (uint32_t t = my_first; t < my_end; t += 8) {        // eight header loads in flight
+        uint32_t c[8];
+#pragma unroll
+        for (uint32_t q = 0; q < 8; ++q) c[q] = ties_of(min(t + q, my_end - 1));
+#pragma unroll
+        for (uint32_t q = 0; q < 8; ++q) my_sum += t + q < my_end ? c[q] : 0u;
+    }
     uint32_t total;
     const uint32_t before = block_exclusive_scan<kFinalBlock>(my_sum, wave_sums, total);
     if (before < krem && krem <= before + my_sum) {
@@ -1320,8 +1393,9 @@ __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restri
                                                            const SegDesc* __restrict__ seg, uint32_t nseg,
                                                            const SegState* __restrict__ state,
                                                            const uint32_t* __restrict__ tile_scope,
-                                                           const u64* __restrict__ rec, u64* __restrict__ mask,
-                                                           u64* __restrict__ tile_state, uint32_t scan_tiles) {
+                                                           const u64* __restrict__ hdrs, const u64* __restrict__ rec,
+                                                           u64* __restrict__ mask, u64* __restrict__ tile_state,
+                                                           uint32_t scan_tiles) {
     __shared__ WalkShared ws[kListBlock / 64];
     // The scan that follows starts from cleared tile states.
     for (u64 j = (u64)blockIdx.x * kListBlock + threadIdx.x; j < scan_tiles; j += (u64)gridDim.x * kListBlock)
@@ -1332,31 +1406,43 @@ __global__ __launch_bounds__(kListBlock) void fixup_kernel(const float* __restri
     uint32_t t_begin, t_end;
     wave_tile_range(num_tiles, blockIdx.x * (kListBlock / 64) + wave, t_begin, t_end);
     for (uint32_t t0 = t_begin; t0 < t_end; t0 += 64) {
-        bool reread = false;      // this lane's tile holds tie-key elements that are kept
-        visit_tiles(w, n, seg, nseg, state, tile_scope, rec, t0, t_end, ws[wave],
-            [&](uint32_t tile, u64 hdr, uint32_t s0, bool) {
-                // The first element of a part has the largest composite its tie-key elements can have.
-                if (header_tie_head(hdr) != 0 && state[s0].tie_key != kNoTieKey &&
-                    composite_of(state[s0].tie_key, tile * kEmitTile) >= state[s0].cstar)
-                    reread = true;
-                if (header_tie_tail(hdr) != 0) {
-                    const uint32_t last = (uint32_t)(min((u64)(tile + 1) * kEmitTile, (u64)n) - 1);
-                    const uint32_t s1 = find_seg(seg, nseg, last);
-                    if (state[s1].tie_key != kNoTieKey && composite_of(state[s1].tie_key, seg[s1].begin) >= state[s1].cstar)
-                        reread = true;
-                }
-            },
+        visit_tiles(w, n, seg, nseg, state, tile_scope, hdrs, rec, t0, t_end, ws[wave],
+            [](uint32_t, u64, uint32_t, bool) {},
             [&](u64 c, uint32_t s) {
                 if (c >= state[s].cstar) {
                     const uint32_t i = index_of(c);
                     atomicOr(&mask[i >> 6], 1ull << (i & 63u));
                 }
             });
+    }
+
+    // Tie-key elements that are kept.  The tiles concerned form runs (all tiles of a constant tensor up to
+    // the one that holds the k-th element), so the waves take tiles at a stride of the whole launch: a
+    // run is shared by all of them.  Lane l looks at the header of the wave's l-th tile.
+    const uint32_t gw = blockIdx.x * (kListBlock / 64) + wave;
+    for (uint32_t base = gw; base < num_tiles; base += 64u * kListWaves) {
+        const u64 tl = (u64)base + (u64)lane * kListWaves;
+        bool reread = false;
+        if (tl < num_tiles) {
+            const uint32_t tile = (uint32_t)tl;
+            const u64 hdr = hdrs[tile];
+            const uint32_t s0 = nseg > 1 ? tile_scope[tile] : 0u;
+            // The first element of a part has the largest composite its tie-key elements can have.
+            if (header_tie_head(hdr) != 0 && state[s0].tie_key != kNoTieKey &&
+                composite_of(state[s0].tie_key, tile * kEmitTile) >= state[s0].cstar)
+                reread = true;
+            if (header_tie_tail(hdr) != 0) {
+                const uint32_t last = (uint32_t)(min((u64)(tile + 1) * kEmitTile, (u64)n) - 1);
+                const uint32_t s1 = find_seg(seg, nseg, last);
+                if (state[s1].tie_key != kNoTieKey && composite_of(state[s1].tie_key, seg[s1].begin) >= state[s1].cstar)
+                    reread = true;
+            }
+        }
         u64 todo = __ballot(reread);
         while (todo != 0) {
             const uint32_t j = (uint32_t)__ffsll((long long)todo) - 1u;
             todo &= todo - 1;
-            const uint32_t tw = t0 + j;
+            const uint32_t tw = base + j * kListWaves;
             const u64 a = (u64)tw * kEmitTile;
             uint32_t sc = nseg > 1 ? tile_scope[tw] : 0u;
             uint32_t sc_end = seg[sc].end;
@@ -1594,7 +1680,7 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
     const uint32_t hist_grid = hist_tiles < s.hist_blocks ? hist_tiles : s.hist_blocks;
     // a record takes what the candidate capacity allows per tile (all of its slots unless a test lowered it)
     const uint32_t per_tile = (uint32_t)(s.cand_cap / emit_tiles);
-    const uint32_t rec_cap = per_tile < kRecSlots - 1 ? per_tile : kRecSlots - 1;
+    const uint32_t rec_cap = per_tile < kRecSlots ? per_tile : kRecSlots;
     // Pass 0 works from (possibly sampled) histograms; pass 1 repeats the five kernels with full
     // counts if a sampled bracket missed, and returns at once otherwise.
     // (A table with no sampled scope cannot miss: the second round is not even launched.)
@@ -1618,7 +1704,7 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
         // with a small grid so that its launch costs little.
         const uint32_t emit_grid = pass == 0 || emit_tiles < 2048 ? emit_tiles : 2048u;
         hipLaunchKernelGGL(emit_kernel, dim3(emit_grid), dim3(kEmitBlock), 0, stream, d_weights, n, s.seg, nseg,
-                           s.state, s.glob, s.tile_scope, s.kept_above, s.rec, rec_cap, d_mask, pass);
+                           s.state, s.glob, s.tile_scope, s.kept_above, s.hdrs, s.rec, rec_cap, d_mask, pass);
         if (pass + 1 == passes && max_small != 0) {
             // after the last emit (it writes the small scopes' words as zero): fork
             hipError_t r = hipEventRecord(s.fork_event, stream);
@@ -1636,18 +1722,18 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
         }
         const uint32_t count_grid = emit_tiles < kCountBlocks ? emit_tiles : kCountBlocks;
         hipLaunchKernelGGL(count1_kernel, dim3(count_grid), dim3(kCountBlock), 0, stream, d_weights, n, s.seg, nseg,
-                           s.state, s.glob, s.tile_scope, s.rec, s.hist1, s.kept_above, s.tie_count, pass);
+                           s.state, s.glob, s.tile_scope, s.hdrs, s.rec, s.hist1, s.kept_above, s.tie_count, pass);
         hipLaunchKernelGGL(select1_kernel, dim3(nseg), dim3(kDigit1Bins / 16), 0, stream, s.seg, s.state, s.hist1,
                            s.kept_above, s.tie_count, s.glob, s.status, pass);
     }
 
     hipLaunchKernelGGL(compact2_kernel, dim3(kMatchBlocks), dim3(kListBlock), 0, stream, d_weights, n, s.seg, nseg,
-                       s.state, s.glob, s.tile_scope, s.rec, s.match, s.match_count, s.status);
+                       s.state, s.glob, s.tile_scope, s.hdrs, s.rec, s.match, s.match_count, s.status);
     hipLaunchKernelGGL(final_kernel, dim3(nseg), dim3(kFinalBlock), 0, stream, d_weights, n, s.seg, nseg, s.state,
-                       s.glob, s.tile_scope, s.rec, s.tie_count, s.match, s.match_count);
+                       s.glob, s.tile_scope, s.hdrs, s.tie_count, s.match, s.match_count);
     const uint32_t scan_tiles = scan_tiles_for(words);
     hipLaunchKernelGGL(fixup_kernel, dim3(kMatchBlocks), dim3(kListBlock), 0, stream, d_weights, n, s.seg, nseg,
-                       s.state, s.tile_scope, s.rec, d_mask, s.tile_state, scan_tiles);
+                       s.state, s.tile_scope, s.hdrs, s.rec, d_mask, s.tile_state, scan_tiles);
     if (max_small != 0) {   // join: the scan reads the small scopes' words
         hipError_t r = hipStreamWaitEvent(stream, s.join_event, 0);
         if (r != hipSuccess) return r;
