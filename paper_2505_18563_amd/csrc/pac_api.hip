@@ -103,13 +103,18 @@ bool is_aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t
 
 uint32_t elem_size(pac_dtype dt) { return dt == PAC_F32 ? 4u : 2u; }
 
-// Stride of the sampled histogram pass over one prune scope: scopes below 4M elements are counted
-// in full; larger ones keep at least about 2M sampled elements, at most one 16384-element tile in 64.
-// 0 marks a small scope.
+// Stride of the sampled histogram pass over one prune scope.  Scopes below 4M elements are counted in
+// full (a table without sampled scopes also needs no retry round).  Larger ones are sampled, one
+// 16384-element tile in `stride`, so that between half a million and a million elements are visited (at
+// most one tile in 64): the sample only has to place the bracket - its rank error of about 1/sqrt(sample)
+// decides how many elements stay undecided in the one full pass - while the pass over the sample costs
+// one LDS atomic per element; with a hundred large scopes and four times this sample it was a quarter of
+// the whole call.  0 marks a small scope.
 uint32_t sample_stride(uint64_t len) {
     if (len <= pac::kSmallScope) return 0;   // small scope: resolved by one workgroup, outside the histogram passes
+    if (len < (1ull << 22)) return 1;
     uint32_t stride = 1;
-    while (stride < pac::kMaxSampleStride && len / (2ull * stride) >= (1ull << 21)) stride *= 2;
+    while (stride < pac::kMaxSampleStride && len / (2ull * stride) >= (1ull << 19)) stride *= 2;
     return stride;
 }
 
