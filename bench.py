@@ -219,6 +219,27 @@ class Bench:
         pac.pac_reduce_local(h, self.compact, self.red, nnz)
         pac.pac_decompress(h, self.red, self.mask, self.prefix, self.dense_out, nnz)
 
+    def fused_step(self, phase: int = 0):
+        """The step with pac_step_fused in place of W x pac_compress + pac_reduce_local."""
+        pac, h, wl = self.pac, self.h, self.wl
+        nnz = pac.pac_build_mask(h, wl.weights, wl.scope_offsets, self.schedule[phase], self.mask, self.prefix)
+        pac.pac_step_fused(h, wl.grads, self.mask, self.prefix, self.red, nnz)
+        pac.pac_decompress(h, self.red, self.mask, self.prefix, self.dense_out, nnz)
+
+    def fused_summary(self, phase: int = 0) -> dict:
+        n, W, e, k = self.n, self.W, self.e, self.k_by_phase[phase]
+        meta = n // 8 + n // 16
+        call_bytes = W * e * n + meta + e * k
+        step_alg = (4 * n + meta) + call_bytes + (e * k + meta + e * n)
+        ms = self.time_call(lambda: self.fused_step(phase))
+        call_ms = self.time_call(lambda: self.pac.pac_step_fused(self.h, self.wl.grads, self.mask, self.prefix, self.red, k))
+        return {"ms_per_step": round(ms, 4), "dense_GBps": round(W * n * e / (ms * 1e-3) / 1e9, 1),
+                "step_algorithmic_GBps": round(step_alg / (ms * 1e-3) / 1e9, 1),
+                "frac": round(step_alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "fused_call_ms": round(call_ms, 4), "fused_call_GBps": round(call_bytes / (call_ms * 1e-3) / 1e9, 1),
+                "note": "pac_step_fused instead of W x compress + reduce_local: a single-GPU upper bound (no per-worker "
+                        "compact buffers, which are what a cluster would send); never `value`"}
+
     def graph_replay_ms(self, phase: int = 0, reps: int = 20) -> float:
         """The whole step (mask build included) replayed from a HIP graph."""
         torch = self.torch
@@ -399,6 +420,7 @@ def main() -> int:
     pac.pac_build_mask(b.h, wl.weights, wl.scope_offsets, b.schedule[0], b.mask, b.prefix)
     cached_ms = b.time_call(b.cached_mask_step)
     graph_ms = b.graph_replay_ms(0)
+    fused = b.fused_summary(0)
 
     k_avg = sum(b.k_by_phase[(args.warmup + t) % nphase] for t in range(args.steps)) / args.steps
     alg = algorithmic_bytes(n, int(k_avg), W, e)
@@ -430,6 +452,7 @@ def main() -> int:
         "device_status_after_timed_steps": status_after_timed,
         "cached_mask_step": {"ms": round(cached_ms, 4), "note": "stable mask: the last mask reused, compress x W + sum + decompress"},
         "graph_replay_step": {"ms": round(graph_ms, 4), "note": "the whole step captured in a HIP graph, 20 replays"},
+        "fused_step": fused,
         "roofline": {
             "kernel": "compress_tile_kernel<unsigned short, 7> (pac_compress)" if wl.dtype == "bf16" else "compress_tile_kernel<unsigned int, 7> (pac_compress)",
             "bound": "hbm",

@@ -163,6 +163,22 @@ pac_status pac_decompress(pac_ctx* ctx, const void* d_compact, pac_dtype dtype, 
                           const uint64_t* d_mask, const uint32_t* d_prefix,
                           void* d_dense_out, uint64_t n, void* hip_stream);
 
+/* (2)+(3) in one pass, for W workers whose dense gradients all lie in THIS GPU's memory: the gather
+ * of pac_compress for each worker and the sum of pac_reduce_local, without the W compact buffers in
+ * between (Sec. III-B / Alg. 1 compress step, the sum of Eq. 1):
+ *   d_reduced[slot(i)] = (((g_0[i] + g_1[i]) + g_2[i]) + ... + g_{W-1}[i])   for every set bit i,
+ * same order, same IEEE single adds, same single rounding for PAC_BF16: bit for bit what
+ * pac_reduce_local gives on the outputs of W pac_compress calls.  It saves writing and re-reading
+ * W * nnz elements and reading the mask and prefix W - 1 times.
+ * This call has no counterpart on a real cluster, where the workers' gradients lie on different GPUs
+ * and the compact buffers are what travels: it measures an upper bound of the single-GPU stand-in
+ * and is reported apart from the four-call path.
+ * h_d_grads is a HOST array of W device pointers (n elements each), read before the call returns.
+ * Device-side checks as in pac_compress.  1 <= W <= PAC_MAX_WORKERS. */
+pac_status pac_step_fused(pac_ctx* ctx, const void* const* h_d_grads, uint32_t W, pac_dtype dtype, uint64_t n,
+                          const uint64_t* d_mask, const uint32_t* d_prefix, void* d_reduced, uint64_t nnz,
+                          void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------
  * Around the hot path: Mask Tracker and weight update.
  * ------------------------------------------------------------------------------------------ */
@@ -262,7 +278,7 @@ pac_status pac_ternary_reduce_local(pac_ctx* ctx, const uint8_t* const* h_d_pack
                                     const float* d_scale, pac_dtype out_dtype, void* d_out, void* hip_stream);
 
 /* Test hook: lower the number of undecided elements pac_build_mask lists between its selection passes
- * (elements in total; each 4096-element tile gets its share, at most 127).  Tiles whose undecided
+ * (elements in total; each 4096-element tile gets its share, at most 128).  Tiles whose undecided
  * elements do not fit are re-read from the weights by the later passes; results are identical.
  * Exists so that tests can reach that branch with small inputs. */
 pac_status pac_debug_set_candidate_capacity(pac_ctx* ctx, uint64_t capacity);

@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     pac_destroy, pac_keep_count, pac_last_error, pac_mask_words, pac_reduce_local,
     MaskTracker, pac_decompress_update, pac_mask_equal, pac_mask_from_nonzero, pac_tracker_create,
     pac_tracker_destroy, pac_tracker_update, pac_absmax, pac_ternarize, pac_ternary_reduce_local,
-    pac_device_status, pac_debug_set_scan_spin_limit, pac_mask_from_nonzero_noalloc, PAC_DEV_SCAN_STALLED, PAC_DEV_COUNT_MISMATCH,
+    pac_step_fused, pac_device_status, pac_debug_set_scan_spin_limit, pac_mask_from_nonzero_noalloc, PAC_DEV_SCAN_STALLED, PAC_DEV_COUNT_MISMATCH,
     PAC_DEV_META_MISMATCH, PAC_DEV_RETRY_TAKEN, PAC_DEV_SLOW_PATH, PAC_DEV_ERROR_MASK, PAC_TABLE_SLOTS,
 )

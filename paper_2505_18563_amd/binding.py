@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.pac_reduce_local.argtypes = [vp, ctypes.POINTER(vp), u32, i32, u64, vp, vp]
     lib.pac_decompress.restype = i32
     lib.pac_decompress.argtypes = [vp, vp, i32, u64, vp, vp, vp, u64, vp]
+    lib.pac_step_fused.restype = i32
+    lib.pac_step_fused.argtypes = [vp, ctypes.POINTER(vp), u32, i32, u64, vp, vp, vp, u64, vp]
     lib.pac_debug_set_candidate_capacity.restype = i32
     lib.pac_debug_set_candidate_capacity.argtypes = [vp, u64]
     lib.pac_debug_set_scan_spin_limit.restype = i32
@@ -221,6 +223,25 @@ def pac_reduce_local(ctx, bufs: Sequence[torch.Tensor], out: torch.Tensor, nnz: 
         raise ValueError("output buffer too short")
     ptrs = (ctypes.c_void_p * max(W, 1))(*[_dev_ptr(b) for b in bufs])
     st = load_library().pac_reduce_local(ctx, ptrs, W, dt, int(nnz), _dev_ptr(out), _stream_ptr(stream))
+    _check(ctx, st)
+
+
+def pac_step_fused(ctx, grads: Sequence[torch.Tensor], mask: torch.Tensor, prefix: torch.Tensor, reduced: torch.Tensor,
+                   nnz: int, stream=None) -> None:
+    """Gather and sum the W dense gradients in one pass: reduced[:nnz] as pac_reduce_local over W pac_compress outputs."""
+    dt = _dtype_code(reduced)
+    W = len(grads)
+    n = grads[0].numel() if W else 0
+    for g in grads:
+        if g.dtype != reduced.dtype:
+            raise TypeError("all gradients and the reduced buffer must share one dtype")
+        if g.numel() != n:
+            raise ValueError("gradients must have equal lengths")
+    if reduced.numel() < nnz:
+        raise ValueError("reduced buffer too short")
+    ptrs = (ctypes.c_void_p * max(W, 1))(*[_dev_ptr(g) for g in grads])
+    st = load_library().pac_step_fused(ctx, ptrs, W, dt, n, _dev_ptr(mask), _dev_ptr(prefix), _dev_ptr(reduced),
+                                       int(nnz), _stream_ptr(stream))
     _check(ctx, st)
 
 
@@ -428,6 +449,12 @@ class PacContext:
         if out is None:
             out = torch.empty(nnz, dtype=bufs[0].dtype, device=self._dev())
         pac_reduce_local(self.handle, bufs, out, nnz, stream)
+        return out
+
+    def step_fused(self, grads: List[torch.Tensor], mask, prefix, nnz: int, out=None, stream=None) -> torch.Tensor:
+        if out is None:
+            out = torch.empty(nnz, dtype=grads[0].dtype, device=self._dev())
+        pac_step_fused(self.handle, grads, mask, prefix, out, nnz, stream)
         return out
 
     def decompress(self, compact, mask, prefix, n, nnz: Optional[int] = None, out=None, stream=None) -> torch.Tensor:

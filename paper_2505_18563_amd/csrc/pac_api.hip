@@ -501,6 +501,37 @@ pac_status pac_reduce_local(pac_ctx* ctx, const void* const* h_d_compact, uint32
     return PAC_OK;
 }
 
+pac_status pac_step_fused(pac_ctx* ctx, const void* const* h_d_grads, uint32_t W, pac_dtype dtype, uint64_t n,
+                          const uint64_t* d_mask, const uint32_t* d_prefix, void* d_reduced, uint64_t nnz,
+                          void* hip_stream) {
+    if (!ctx) return PAC_ERR_ARG;
+    const char* who = "pac_step_fused";
+    if (dtype != PAC_F32 && dtype != PAC_BF16) return fail(ctx, PAC_ERR_ARG, "%s: unknown dtype %d", who, (int)dtype);
+    if (W < 1 || W > PAC_MAX_WORKERS) return fail(ctx, PAC_ERR_RANGE, "%s: W=%u not in [1, %u]", who, W, PAC_MAX_WORKERS);
+    if (n >= (1ull << 32)) return fail(ctx, PAC_ERR_RANGE, "%s: n=%llu must be below 2^32", who, (unsigned long long)n);
+    if (nnz > n) return fail(ctx, PAC_ERR_COUNT, "%s: nnz=%llu exceeds n=%llu", who, (unsigned long long)nnz, (unsigned long long)n);
+    if (!h_d_grads) return fail(ctx, PAC_ERR_ARG, "%s: pointer table is NULL", who);
+    if (n == 0) return PAC_OK;
+    if (!d_mask || !d_prefix || (nnz > 0 && !d_reduced)) return fail(ctx, PAC_ERR_ARG, "%s: NULL device pointer", who);
+    const uint32_t es = elem_size(dtype);
+    if (!is_aligned(d_reduced, es) || !is_aligned(d_mask, 8) || !is_aligned(d_prefix, 4))
+        return fail(ctx, PAC_ERR_ALIGN, "%s: pointer not aligned to its element size", who);
+    pac::WorkerPtrs bufs;
+    for (uint32_t w = 0; w < PAC_MAX_WORKERS; ++w) bufs.p[w] = nullptr;
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!h_d_grads[w]) return fail(ctx, PAC_ERR_ARG, "%s: gradient %u is NULL", who, w);
+        if (!is_aligned(h_d_grads[w], es)) return fail(ctx, PAC_ERR_ALIGN, "%s: gradient %u misaligned", who, w);
+        bufs.p[w] = h_d_grads[w];
+    }
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: hipSetDevice: %s", who, hipGetErrorString(guard.status));
+    hipError_t r = pac::launch_step_fused(bufs, W, (int)dtype, (uint32_t)n, reinterpret_cast<const unsigned long long*>(d_mask),
+                                          d_prefix, d_reduced, (uint32_t)nnz, ctx->scratch.status,
+                                          static_cast<hipStream_t>(hip_stream));
+    if (r != hipSuccess) return fail(ctx, PAC_ERR_HIP, "%s: launch: %s", who, hipGetErrorString(r));
+    return PAC_OK;
+}
+
 // ---- Mask Tracker and weight update ----------------------------------------------------------
 
 pac_status pac_mask_from_nonzero(pac_ctx* ctx, const void* d_values, pac_dtype dtype, uint64_t n, uint64_t* d_mask,

@@ -210,4 +210,10 @@ hipError_t launch_ternary_reduce(const WorkerPtrs& bufs, uint32_t W, uint32_t co
 hipError_t launch_reduce(const WorkerPtrs& bufs, uint32_t W, int dtype, uint32_t nnz, void* d_out,
                          hipStream_t stream);
 
+// reduced[slot(i)] = ((g_0[i] + g_1[i]) + ...) + g_{W-1}[i] for kept i: gather and sum in one pass over the W
+// dense gradients.
+hipError_t launch_step_fused(const WorkerPtrs& grads, uint32_t W, int dtype, uint32_t n,
+                             const unsigned long long* d_mask, const uint32_t* d_prefix, void* d_reduced, uint32_t nnz,
+                             uint32_t* d_status, hipStream_t stream);
+
 }  // namespace pac

@@ -605,6 +605,194 @@ __global__ __launch_bounds__(kBlock) void reduce_scalar_kernel(WorkerPtrs bufs, 
     store_scalar<DT>(out, (uint32_t)j, a);
 }
 
+// ------------------------------------------------------------------------- fused gather + sum
+// compress for each of the W workers followed by the sum, without the W compact buffers in between:
+// a lane keeps the running sums of its chunks' elements in registers - every element, kept or not; the
+// adds are cheap next to the loads - walks the workers in order (worker 0's value first, then one IEEE
+// single add per further worker: the order and the arithmetic of reduce_vec_kernel), and only the final
+// sums of the kept elements go through the LDS staging area into the reduced buffer, as in
+// compress_tile_kernel.  Mask words and prefix entries are read once per tile instead of once per worker.
+// Tiles of 4096 elements (64 mask words): 2 chunks per lane for bf16, 4 for fp32; the loads of 4 workers
+// are in flight together.
+template <typename T>
+struct FusedShape;
+template <>
+struct FusedShape<uint16_t> { static constexpr int U = 2, G = 4; };   // measured: 6.3 TB/s on 16 bf16 streams; 4 x 4 and 2 x 8 the same, 1 x 8 slower
+template <>
+struct FusedShape<uint32_t> { static constexpr int U = 4, G = 4; };   // measured: 4 x 4 5.6 TB/s on 8 fp32 streams at s = 0.5, 4 x 2 5.1
+
+template <typename T>
+struct FusedAcc;
+template <>
+struct FusedAcc<uint32_t> {
+    float a[4];
+    __device__ __forceinline__ void set(const u32x4& v) {
+        a[0] = __uint_as_float(v.x); a[1] = __uint_as_float(v.y); a[2] = __uint_as_float(v.z); a[3] = __uint_as_float(v.w);
+    }
+    __device__ __forceinline__ void add(const u32x4& v) {
+        a[0] = __fadd_rn(a[0], __uint_as_float(v.x)); a[1] = __fadd_rn(a[1], __uint_as_float(v.y));
+        a[2] = __fadd_rn(a[2], __uint_as_float(v.z)); a[3] = __fadd_rn(a[3], __uint_as_float(v.w));
+    }
+    __device__ __forceinline__ uint32_t get(int e) const { return __float_as_uint(a[e]); }
+};
+template <>
+struct FusedAcc<uint16_t> {
+    float a[8];
+    __device__ __forceinline__ void set(const u32x4& v) {
+        const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[2 * i] = __uint_as_float(d[i] << 16);
+            a[2 * i + 1] = __uint_as_float(d[i] & 0xFFFF0000u);
+        }
+    }
+    __device__ __forceinline__ void add(const u32x4& v) {
+        const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[2 * i] = __fadd_rn(a[2 * i], __uint_as_float(d[i] << 16));
+            a[2 * i + 1] = __fadd_rn(a[2 * i + 1], __uint_as_float(d[i] & 0xFFFF0000u));
+        }
+    }
+    __device__ __forceinline__ uint16_t get(int e) const { return (uint16_t)f32_to_bf16_bits(a[e]); }
+};
+
+template <typename T>
+__global__ __launch_bounds__(kCompressBlock) void fused_tile_kernel(WorkerPtrs grads, uint32_t W, uint32_t n,
+                                                                    const unsigned long long* __restrict__ mask,
+                                                                    const uint32_t* __restrict__ prefix,
+                                                                    T* __restrict__ out, uint32_t nnz,
+                                                                    uint32_t* __restrict__ status) {
+    constexpr int U = FusedShape<T>::U, G = FusedShape<T>::G;
+    typedef BlockTile<T, U> Geo;
+    constexpr uint32_t E = Geo::E;
+    constexpr int DT = sizeof(T) == 4 ? 0 : 1;
+    __shared__ __attribute__((aligned(16))) T stage[Geo::kStage];
+
+    const uint32_t tile = blockIdx.x;
+    const uint32_t n_chunks = n / E;
+    const uint32_t words = (uint32_t)(((unsigned long long)n + 63) >> 6);
+    const uint32_t chunk0 = tile * Geo::kChunks;
+    uint32_t q[U];
+    bool live[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        q[u] = chunk0 + (uint32_t)u * kCompressBlock + threadIdx.x;
+        live[u] = q[u] < n_chunks;
+    }
+
+    // the sums, workers in order, G workers' loads in flight
+    FusedAcc<T> acc[U];
+    {
+        const u32x4* g0 = static_cast<const u32x4*>(grads.p[0]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u].set(live[u] ? __builtin_nontemporal_load(g0 + q[u]) : (u32x4){0, 0, 0, 0});
+    }
+    uint32_t w = 1;
+    for (; w + G <= W; w += G) {
+        u32x4 v[G][U];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const u32x4* gp = static_cast<const u32x4*>(grads.p[w + g]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[g][u] = live[u] ? __builtin_nontemporal_load(gp + q[u]) : (u32x4){0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[u].add(v[g][u]);
+    }
+    for (; w < W; ++w) {
+        const u32x4* gp = static_cast<const u32x4*>(grads.p[w]);
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = live[u] ? __builtin_nontemporal_load(gp + q[u]) : (u32x4){0, 0, 0, 0};
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u].add(v[u]);
+    }
+
+    // the kept sums into the tile's compact range, as in compress_tile_kernel
+    const uint32_t w0 = tile * Geo::kWords;   // < words by the launch shape
+    const uint32_t w1 = w0 + Geo::kWords;
+    const uint32_t s0 = prefix[w0];
+    const uint32_t s1 = w1 < words ? prefix[w1] : nnz;
+    if (tile == gridDim.x - 1 && threadIdx.x == 0) check_total(mask, prefix, words, nnz, status);
+    if (s0 > s1 || s1 > nnz || s1 - s0 > Geo::kElems) {   // same decision in every thread
+        if (threadIdx.x == 0) atomicOr(status, kDevMetaMismatch);
+        return;
+    }
+    const uint32_t count = s1 - s0;
+    const uint32_t ph = phase_of(out + s0);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (live[u]) {
+            const uint32_t wd = (q[u] * E) >> 6;
+            const unsigned long long word = mask[wd];
+            const uint32_t bitoff = (q[u] * E) & 63u;
+            uint32_t sub = (uint32_t)(word >> bitoff) & ((1u << E) - 1u);
+            const uint32_t pos = prefix[wd] + popc64(word & ((1ull << bitoff) - 1ull)) - s0 + ph;
+            if (pos > Geo::kStage - E) sub = 0;
+            T* p = stage + pos;
+#pragma unroll
+            for (int e = 0; e < (int)E; ++e) {
+                if (sub & (1u << e)) {
+                    *p = acc[u].get(e);
+                    ++p;
+                }
+            }
+        }
+    }
+    // Elements after the last whole chunk (n not a multiple of E) belong to the tile they follow.
+    if (tile == n_chunks / Geo::kChunks) {
+        const uint32_t i = n_chunks * E + threadIdx.x;
+        if (threadIdx.x < E && i < n) {
+            const unsigned long long wd = mask[i >> 6];
+            if ((wd >> (i & 63u)) & 1ull) {
+                float a = load_scalar<DT>(grads.p[0], i);
+                for (uint32_t ww = 1; ww < W; ++ww) a = __fadd_rn(a, load_scalar<DT>(grads.p[ww], i));
+                const uint32_t pos = prefix[i >> 6] + popc64(wd & ((1ull << (i & 63u)) - 1ull)) - s0 + ph;
+                if (pos < Geo::kStage) stage[pos] = DT == 0 ? (T)__float_as_uint(a) : (T)f32_to_bf16_bits(a);
+            }
+        }
+    }
+    __syncthreads();
+
+    // LDS [ph, ph + count) -> out [s0, s1); (out + s0 - ph) is 16-byte aligned.
+    T* gbase = out + s0 - ph;
+    const uint32_t a = ph, b = ph + count;
+    uint32_t h_end = (a + E - 1u) & ~(E - 1u);
+    if (h_end > b) h_end = b;
+    if (threadIdx.x < h_end - a) gbase[a + threadIdx.x] = stage[a + threadIdx.x];
+    for (uint32_t c = h_end / E + threadIdx.x; c < b / E; c += kCompressBlock)
+        *reinterpret_cast<u32x4*>(gbase + c * E) = *reinterpret_cast<const u32x4*>(stage + c * E);   // read next by pac_decompress
+    uint32_t t0 = b & ~(E - 1u);
+    if (t0 < h_end) t0 = h_end;
+    if (threadIdx.x < b - t0) gbase[t0 + threadIdx.x] = stage[t0 + threadIdx.x];
+}
+
+// Any element alignment: one element per lane.
+template <int DT, typename T>
+__global__ __launch_bounds__(kBlock) void fused_scalar_kernel(WorkerPtrs grads, uint32_t W, uint32_t n,
+                                                              const unsigned long long* __restrict__ mask,
+                                                              const uint32_t* __restrict__ prefix, T* __restrict__ out,
+                                                              uint32_t nnz, uint32_t* __restrict__ status) {
+    const unsigned long long i = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    if (i == n - 1) check_total(mask, prefix, (uint32_t)(((unsigned long long)n + 63) >> 6), nnz, status);
+    const unsigned long long wd = mask[i >> 6];
+    const uint32_t b = (uint32_t)i & 63u;
+    if ((wd >> b) & 1ull) {
+        const uint32_t slot = prefix[i >> 6] + popc64(wd & ((1ull << b) - 1ull));
+        if (slot < nnz) {
+            float a = load_scalar<DT>(grads.p[0], (uint32_t)i);
+            for (uint32_t w = 1; w < W; ++w) a = __fadd_rn(a, load_scalar<DT>(grads.p[w], (uint32_t)i));
+            store_scalar<DT>(out, slot, a);
+        } else {
+            atomicOr(status, kDevMetaMismatch);
+        }
+    }
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline uint32_t div_up(unsigned long long a, unsigned long long b) { return (uint32_t)((a + b - 1) / b); }
@@ -693,6 +881,34 @@ hipError_t launch_decompress_update(const void* d_compact, int dtype, uint32_t n
         else
             hipLaunchKernelGGL((update_scalar_kernel<uint16_t>), dim3(blocks), dim3(kBlock), 0, stream,
                                static_cast<const uint16_t*>(d_compact), nnz, d_mask, d_prefix, alpha, d_weights, n, d_status);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_step_fused(const WorkerPtrs& grads, uint32_t W, int dtype, uint32_t n,
+                             const unsigned long long* d_mask, const uint32_t* d_prefix, void* d_reduced, uint32_t nnz,
+                             uint32_t* d_status, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    bool vec = true;
+    for (uint32_t w = 0; w < W; ++w) vec = vec && aligned16(grads.p[w]);
+    if (vec) {
+        if (dtype == 0) {
+            const uint32_t tiles = div_up(n, BlockTile<uint32_t, FusedShape<uint32_t>::U>::kElems);
+            hipLaunchKernelGGL((fused_tile_kernel<uint32_t>), dim3(tiles), dim3(kCompressBlock), 0, stream, grads, W, n,
+                               d_mask, d_prefix, static_cast<uint32_t*>(d_reduced), nnz, d_status);
+        } else {
+            const uint32_t tiles = div_up(n, BlockTile<uint16_t, FusedShape<uint16_t>::U>::kElems);
+            hipLaunchKernelGGL((fused_tile_kernel<uint16_t>), dim3(tiles), dim3(kCompressBlock), 0, stream, grads, W, n,
+                               d_mask, d_prefix, static_cast<uint16_t*>(d_reduced), nnz, d_status);
+        }
+    } else {
+        const uint32_t blocks = div_up(n, kBlock);
+        if (dtype == 0)
+            hipLaunchKernelGGL((fused_scalar_kernel<0, uint32_t>), dim3(blocks), dim3(kBlock), 0, stream, grads, W, n,
+                               d_mask, d_prefix, static_cast<uint32_t*>(d_reduced), nnz, d_status);
+        else
+            hipLaunchKernelGGL((fused_scalar_kernel<1, uint16_t>), dim3(blocks), dim3(kBlock), 0, stream, grads, W, n,
+                               d_mask, d_prefix, static_cast<uint16_t*>(d_reduced), nnz, d_status);
     }
     return hipGetLastError();
 }
