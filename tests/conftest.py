@@ -10,3 +10,5 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # a limit per test where the pytest-timeout plugin is installed; a plain, harmless marker where it is not
+    config.addinivalue_line("markers", "timeout(seconds): time limit of one test (pytest-timeout)")

@@ -78,3 +78,18 @@ def test_product_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+
+
+def test_per_tensor_keep_totals_of_the_configurations(pac):
+    """nnz of a per-tensor prune = sum of the tensors' keep counts: the library's host rule and the oracle's
+    against the totals worked by exact arithmetic (tests/golden/keep_totals_per_tensor.txt)."""
+    import oracle
+    from synth.shapes import config_shapes, flat_size
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "keep_totals_per_tensor.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 9
+    for cid, n, s, total in rows:
+        specs = config_shapes(int(cid))
+        assert flat_size(specs) == int(n)
+        assert sum(pac.pac_keep_count(t.numel, float(s)) for t in specs) == int(total)
+        assert sum(oracle.keep_count(t.numel, float(s)) for t in specs) == int(total)
