@@ -351,17 +351,20 @@ pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n, cons
 
     // Keep counts: host arithmetic, so the total is known without waiting for the device.
     std::vector<pac::SegDesc> table(nseg);
-    uint64_t total = 0, sampled = 0;
+    uint64_t total = 0;
+    uint32_t slots0 = 0, slots1 = 0;   // work items of the sampled and of the full histogram pass
     bool any_sampled = false;
     uint32_t max_small = 0, max_tiny = 0;   // longest small scope of the table, and longest of the tiny class
     for (uint32_t s = 0; s < nseg; ++s) {
         const uint64_t b = h_seg_offsets[s], e = h_seg_offsets[s + 1];
         const uint64_t k = pac_keep_count(e - b, h_sparsity[s]);
-        table[s] = pac::SegDesc{(uint32_t)b, (uint32_t)e, (uint32_t)k, sample_stride(e - b)};
+        table[s] = pac::SegDesc{(uint32_t)b, (uint32_t)e, (uint32_t)k, sample_stride(e - b), slots0, slots1};
         total += k;
         if (table[s].stride > 1) any_sampled = true;
-        if (table[s].stride != 0) sampled += (e - b) / table[s].stride;
-        else {
+        if (table[s].stride != 0) {
+            slots0 += pac::hist_slots((uint32_t)b, (uint32_t)e, table[s].stride);
+            slots1 += pac::hist_slots((uint32_t)b, (uint32_t)e, 1);
+        } else {
             if (e - b > max_small) max_small = (uint32_t)(e - b);
             if (e - b <= pac::kTinyScope && e - b > max_tiny) max_tiny = (uint32_t)(e - b);
         }
@@ -425,7 +428,7 @@ pac_status pac_build_mask(pac_ctx* ctx, const float* d_weights, uint64_t n, cons
     pac::MaskScratch call = ctx->scratch;
     call.seg = slot->d_seg;
     call.tile_scope = slot->d_tile_scope;
-    hipError_t r = pac::launch_build_mask(call, d_weights, (uint32_t)n, nseg, sampled, any_sampled, max_tiny, max_small,
+    hipError_t r = pac::launch_build_mask(call, d_weights, (uint32_t)n, nseg, slots0, slots1, any_sampled, max_tiny, max_small,
                                           fresh, reinterpret_cast<unsigned long long*>(d_mask), d_prefix, total, stream);
     if (r != hipSuccess) {
         if (fresh) slot->valid = false;   // its tile_scope may not have been filled

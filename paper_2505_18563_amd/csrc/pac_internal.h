@@ -34,7 +34,21 @@ struct SegDesc {
     uint32_t stride;   // the first histogram pass visits one tile in `stride` (power of two; 1 = every tile);
                        // 0 marks a small scope (at most kSmallScope elements), which takes no part in the
                        // histogram passes: one workgroup selects and writes its mask bits from LDS
+    uint32_t slot0;    // work items ("slots") of the histogram passes before this scope: in the first pass one slot
+    uint32_t slot1;    // per aligned group of `stride` tiles that the scope touches (slot0), in the full pass one
+                       // per tile that it touches (slot1).  See hist_slots().
 };
+
+// Tiles of the histogram passes: kHistTileElems consecutive flat elements, counted from element 0 of the flat
+// tensor (not from the scope's begin).  A scope at stride m takes part in the first pass with one tile of every
+// aligned group of m tiles; the number of such groups (m = 1: of tiles) that [begin, end) touches:
+constexpr uint32_t kHistTileElems = 16384;
+inline uint32_t hist_slots(uint32_t begin, uint32_t end, uint32_t m) {
+    if (m == 0 || begin >= end) return 0;
+    uint32_t sh = 0;
+    while ((1u << sh) < m) ++sh;
+    return (((end - 1) / kHistTileElems) >> sh) - ((begin / kHistTileElems) >> sh) + 1;
+}
 
 // Selection state of one prune scope, device only.
 constexpr uint32_t kNoTieKey = 0xFFFFFFFFu;   // no key is 0xFFFFFFFF (keys have 31 bits)
@@ -136,7 +150,7 @@ constexpr uint32_t kTinyScope = 4096;
 // `fresh_table`: s.tile_scope has not been filled for the table in s.seg yet.  `expect_total`: the sum of
 // the scopes' keep counts (the scan raises kDevCountMismatch if the mask holds another number of bits).
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
-                             uint64_t sampled_elems, bool any_sampled, uint32_t max_tiny, uint32_t max_small,
+                             uint32_t slots0, uint32_t slots1, bool any_sampled, uint32_t max_tiny, uint32_t max_small,
                              bool fresh_table, unsigned long long* d_mask, uint32_t* d_prefix,
                              unsigned long long expect_total, hipStream_t stream);
 // Raises the small-scope kernel's LDS limit; once per device, before the first launch.

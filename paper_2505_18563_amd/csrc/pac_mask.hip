@@ -48,27 +48,6 @@ __device__ __forceinline__ uint32_t hash32(uint32_t x) {
     x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
     return x;
 }
-// Whether the sampled histogram pass visits tile t at stride m (a power of two): one tile of every
-// aligned group of m, at a hashed position so that no period of the tensor layout can line up with it.
-__device__ __forceinline__ bool tile_sampled(uint32_t t, uint32_t m) {
-    if (m <= 1) return true;
-    const uint32_t group = t >> (31 - __clz((int)m));   // t / m
-    return (t & (m - 1)) == (hash32(group) & (m - 1));
-}
-
-// The first tile >= t that tile_sampled() accepts at stride m.
-__device__ __forceinline__ uint32_t next_sampled(uint32_t t, uint32_t m) {
-    if (m <= 1) return t;
-    const uint32_t shift = 31 - __clz((int)m);
-    uint32_t group = t >> shift;
-    uint32_t cand = (group << shift) + (hash32(group) & (m - 1));
-    if (cand < t) {
-        ++group;
-        cand = (group << shift) + (hash32(group) & (m - 1));
-    }
-    return cand;
-}
-
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
 __device__ __forceinline__ uint32_t lanes_below(u64 m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
@@ -148,6 +127,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* w
 constexpr int kHistBlock = 1024;
 constexpr uint32_t kHistLoads = 4;                                 // 16-byte loads per thread per tile
 constexpr uint32_t kHistTile = kHistBlock * 4 * kHistLoads;        // 16384 elements
+static_assert(kHistTile == kHistTileElems, "the host counts histogram work in tiles of this size");
 
 // ++lds[d] for every lane with `active`.  LDS atomics on one address are serialised lane by lane, and a
 // tensor with very many equal magnitudes (the zeros of a pruned model) sends most lanes of every wave to
@@ -189,11 +169,24 @@ __device__ __forceinline__ void hist0_range(const float* __restrict__ w, u64 fro
     }
 }
 
+// First slot of scope s in the given pass; nseg stands for "one past the last scope".
+__device__ __forceinline__ uint32_t first_slot(const SegDesc* __restrict__ seg, uint32_t nseg, uint32_t s,
+                                               uint32_t pass, uint32_t total_slots) {
+    if (s >= nseg) return total_slots;
+    return pass == 0 ? seg[s].slot0 : seg[s].slot1;
+}
+
+// The work of a histogram pass is a list of slots: per scope (in order) one slot for every aligned group
+// of `stride` tiles that the scope touches - in the full pass, and for a scope counted in full, for every
+// tile.  A slot stands for the group's sampled tile, clipped to the scope, or for nothing when that tile
+// lies outside the scope (first and last group only).  The workgroups share the slots evenly, each taking
+// a run of consecutive ones, so that the work is balanced whatever mix of strides the table holds, a
+// workgroup meets few scope boundaries, and flushes its histogram rarely.
 template <bool VEC>
 __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restrict__ w, uint32_t n,
                                                            const SegDesc* __restrict__ seg, uint32_t nseg,
                                                            uint32_t* __restrict__ hist0, Globals* glob,
-                                                           uint32_t pass) {
+                                                           uint32_t pass, uint32_t total_slots) {
     __shared__ uint32_t lds[kDigit0Bins];
     if (pass != 0 && !glob->retry) return;             // the retry pass has nothing to do
     for (uint32_t b = threadIdx.x; b < kDigit0Bins; b += kHistBlock) lds[b] = 0;
@@ -207,86 +200,64 @@ __global__ __launch_bounds__(kHistBlock) void hist0_kernel(const float* __restri
     }
     __syncthreads();
 
-    const uint32_t num_tiles = (uint32_t)(((u64)n + kHistTile - 1) / kHistTile);
-    const uint32_t kNone = 0xFFFFFFFFu;
-    uint32_t cur = kNone;   // scope whose counts sit in the LDS histogram
-    uint32_t cur_begin = 0, cur_end = 0, cur_stride = 1;
+    const uint32_t per_block = (total_slots + gridDim.x - 1) / gridDim.x;
+    const uint32_t j_begin = blockIdx.x * per_block;
+    const uint32_t j_end = min(total_slots, j_begin + per_block);
+    if (j_begin >= j_end) return;
 
-    // Each workgroup owns one contiguous range of tiles, so it meets few scope boundaries and
-    // flushes its histogram rarely.
-    const uint32_t per_block = (num_tiles + gridDim.x - 1) / gridDim.x;
-    const uint32_t t_begin = blockIdx.x * per_block;
-    const uint32_t t_end = min(num_tiles, t_begin + per_block);
-    for (uint32_t t = t_begin; t < t_end; ++t) {
-        const uint32_t a = t * kHistTile;
-        const uint32_t b = (uint32_t)min((u64)a + kHistTile, (u64)n);
-        uint32_t s = cur;
-        if (cur == kNone || a < cur_begin || a >= cur_end) s = find_seg(seg, nseg, a);
-        const uint32_t s_end = s == cur ? cur_end : seg[s].end;
-        if (s_end >= b) {
-            const uint32_t raw_stride = s == cur ? cur_stride : seg[s].stride;
-            if (raw_stride == 0) continue;              // small scope: not part of the histogram passes
-            if (s != cur) {
-                if (cur != kNone) flush_hist0(lds, hist0 + (size_t)cur * kDigit0Bins);
-                cur = s;
-                cur_begin = seg[s].begin;
-                cur_end = s_end;
-                cur_stride = raw_stride;
-            }
-            if (pass == 0 && raw_stride > 1) {
-                // Go straight to the scope's next sampled tile.  Every wave of the chip runs this
-                // loop, and a compute unit issues one scalar instruction per clock for all of its
-                // waves together, so stepping over the unsampled tiles one by one would cost more
-                // than the sampled tiles' loads.
-                const uint32_t next = next_sampled(t, raw_stride);
-                if (next != t) {
-                    // The tiles before cur_end / kHistTile are whole tiles of this scope.  A ragged
-                    // last tile is its own "first tile not wholly inside": step past it.
-                    const uint32_t past_whole = cur_end / kHistTile;
-                    t = max(min(next, past_whole), t + 1) - 1;   // the loop adds the 1 back
-                    continue;
-                }
-            }
-            if (VEC && b - a == kHistTile) {
-                const u32x4* p = reinterpret_cast<const u32x4*>(w + a) + threadIdx.x;
-                u32x4 v[kHistLoads];
+    // The scope that owns slot j_begin: the last one whose first slot is <= j_begin (scopes without slots
+    // share their first slot with the scope after them).
+    uint32_t s;
+    {
+        uint32_t lo = 0, hi = nseg - 1;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi + 1) >> 1;
+            if (first_slot(seg, nseg, mid, pass, total_slots) <= j_begin) lo = mid; else hi = mid - 1;
+        }
+        s = lo;
+    }
+    const uint32_t kNone = 0xFFFFFFFFu;
+    uint32_t counted = kNone;   // scope whose counts sit in the LDS histogram
+    uint32_t s_first = first_slot(seg, nseg, s, pass, total_slots);
+    uint32_t s_next = first_slot(seg, nseg, s + 1, pass, total_slots);
+    uint32_t sb = seg[s].begin, se = seg[s].end, m = pass == 0 ? seg[s].stride : 1u;
+    for (uint32_t j = j_begin; j < j_end; ++j) {
+        while (j >= s_next) {                           // s_next <= total_slots > j for the last scope: ends
+            ++s;
+            s_first = s_next;
+            s_next = first_slot(seg, nseg, s + 1, pass, total_slots);
+            sb = seg[s].begin; se = seg[s].end; m = pass == 0 ? seg[s].stride : 1u;
+        }
+        const uint32_t sh = 31 - __clz((int)m);         // m is a power of two >= 1 for a scope with slots
+        const uint32_t first_tile = sb / kHistTile, last_tile = (se - 1) / kHistTile;
+        const uint32_t group = (first_tile >> sh) + (j - s_first);
+        // one tile of every aligned group of m, at a hashed position so that no period of the tensor
+        // layout can line up with the sample
+        const uint32_t t = (group << sh) + (hash32(group) & (m - 1));
+        if (t < first_tile || t > last_tile) continue;
+        if (s != counted) {
+            if (counted != kNone) flush_hist0(lds, hist0 + (size_t)counted * kDigit0Bins);
+            counted = s;
+        }
+        const u64 a = max((u64)t * kHistTile, (u64)sb);
+        const u64 b = min(((u64)t + 1) * kHistTile, (u64)se);
+        if (VEC && b - a == kHistTile) {
+            const u32x4* p = reinterpret_cast<const u32x4*>(w + a) + threadIdx.x;
+            u32x4 v[kHistLoads];
 #pragma unroll
-                for (uint32_t u = 0; u < kHistLoads; ++u) v[u] = __builtin_nontemporal_load(p + u * kHistBlock);
+            for (uint32_t u = 0; u < kHistLoads; ++u) v[u] = __builtin_nontemporal_load(p + u * kHistBlock);
 #pragma unroll
-                for (uint32_t u = 0; u < kHistLoads; ++u) {
-                    count_digit0(lds, digit0_of(key_of_bits(v[u].x)), true);
-                    count_digit0(lds, digit0_of(key_of_bits(v[u].y)), true);
-                    count_digit0(lds, digit0_of(key_of_bits(v[u].z)), true);
-                    count_digit0(lds, digit0_of(key_of_bits(v[u].w)), true);
-                }
-            } else {
-                hist0_range(w, a, b, lds);
+            for (uint32_t u = 0; u < kHistLoads; ++u) {
+                count_digit0(lds, digit0_of(key_of_bits(v[u].x)), true);
+                count_digit0(lds, digit0_of(key_of_bits(v[u].y)), true);
+                count_digit0(lds, digit0_of(key_of_bits(v[u].z)), true);
+                count_digit0(lds, digit0_of(key_of_bits(v[u].w)), true);
             }
         } else {
-            // The tile crosses scope boundaries: one sub-range per scope, each under its own scope's
-            // sampling rule, through the LDS histogram like a whole tile.
-            uint32_t sc = s, pos = a;
-            while (pos < b) {                           // the last scope ends at n >= b
-                const uint32_t sb = seg[sc].begin, se = seg[sc].end, sstride = seg[sc].stride;
-                if (se > pos) {
-                    const uint32_t upto = min(se, b);
-                    if (sstride != 0 && (pass != 0 || tile_sampled(t, sstride))) {
-                        if (sc != cur) {
-                            if (cur != kNone) flush_hist0(lds, hist0 + (size_t)cur * kDigit0Bins);
-                            cur = sc;
-                            cur_begin = sb;
-                            cur_end = se;
-                            cur_stride = sstride;
-                        }
-                        hist0_range(w, pos, upto, lds);
-                    }
-                    pos = upto;
-                }
-                ++sc;
-            }
+            hist0_range(w, a, b, lds);
         }
     }
-    if (cur != kNone) flush_hist0(lds, hist0 + (size_t)cur * kDigit0Bins);
+    if (counted != kNone) flush_hist0(lds, hist0 + (size_t)counted * kDigit0Bins);
 }
 
 // ---------------------------------------------------------------------------- select0 / select1
@@ -1665,19 +1636,18 @@ hipError_t launch_status_read(uint32_t* d_status, uint32_t* d_out, bool clear, h
 }
 
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
-                             uint64_t sampled_elems, bool any_sampled, uint32_t max_tiny, uint32_t max_small,
+                             uint32_t slots0, uint32_t slots1, bool any_sampled, uint32_t max_tiny, uint32_t max_small,
                              bool fresh_table, unsigned long long* d_mask, uint32_t* d_prefix,
                              unsigned long long expect_total, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     const uint32_t words = div_up_u64(n, 64);
     const bool aligned = (reinterpret_cast<uintptr_t>(d_weights) & 15u) == 0;
-    const uint32_t hist_tiles = div_up_u64(n, kHistTile), emit_tiles = div_up_u64(n, kEmitTile);
+    const uint32_t emit_tiles = div_up_u64(n, kEmitTile);
 
     if (fresh_table && nseg > 1)
         hipLaunchKernelGGL(tile_scope_kernel, dim3(div_up_u64(emit_tiles, 256)), dim3(256), 0, stream, s.seg, nseg,
                            emit_tiles, s.tile_scope);
 
-    const uint32_t hist_grid = hist_tiles < s.hist_blocks ? hist_tiles : s.hist_blocks;
     // a record takes what the candidate capacity allows per tile (all of its slots unless a test lowered it)
     const uint32_t per_tile = (uint32_t)(s.cand_cap / emit_tiles);
     const uint32_t rec_cap = per_tile < kRecSlots ? per_tile : kRecSlots;
@@ -1686,18 +1656,17 @@ hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint3
     // (A table with no sampled scope cannot miss: the second round is not even launched.)
     const uint32_t passes = any_sampled ? 2u : 1u;
     for (uint32_t pass = 0; pass < passes; ++pass) {
-        // The sampled pass visits few tiles: no more workgroups than tiles.
-        uint32_t grid = hist_grid;
-        if (pass == 0) {
-            const uint32_t visited = div_up_u64(sampled_elems, kHistTile);
-            if (visited < grid) grid = visited < 1 ? 1 : visited;
-        }
+        // No more workgroups than fit on the device at once, nor than there are slots (the sampled pass
+        // has few).  A table of small scopes only has no slot: one workgroup still clears the counters.
+        const uint32_t slots = pass == 0 ? slots0 : slots1;
+        uint32_t grid = slots < s.hist_blocks ? slots : s.hist_blocks;
+        if (grid == 0) grid = 1;
         if (aligned)
             hipLaunchKernelGGL((hist0_kernel<true>), dim3(grid), dim3(kHistBlock), 0, stream, d_weights, n,
-                               s.seg, nseg, s.hist0, s.glob, pass);
+                               s.seg, nseg, s.hist0, s.glob, pass, slots);
         else
             hipLaunchKernelGGL((hist0_kernel<false>), dim3(grid), dim3(kHistBlock), 0, stream, d_weights, n,
-                               s.seg, nseg, s.hist0, s.glob, pass);
+                               s.seg, nseg, s.hist0, s.glob, pass, slots);
         hipLaunchKernelGGL(select0_kernel, dim3(nseg), dim3(kDigit0Bins / 16), 0, stream, d_weights, s.seg, s.state,
                            s.hist0, s.kept_above, s.tie_count, s.glob, pass);
         // One workgroup per tile; the retry pass, which almost never runs, strides over the tiles
