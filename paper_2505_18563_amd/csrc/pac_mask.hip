@@ -2,31 +2,36 @@
 //
 // Per prune scope the kept set is "the k largest composites" (see pac_internal.h); C* is the k-th.
 //
-//   hist0    histogram of digit 0 per scope (LDS histograms flushed to a global one).  Large scopes
-//            are only sampled: one 16384-element tile in `stride`, at a hashed position
-//   select0  per scope: bracket [lo, hi) of whole digit-0 bins that holds the k-th key - exactly
-//            one bin when every element was counted, the bins inside a confidence band around the
-//            estimated rank when the scope was sampled
+//   hist0    histogram of digit 0 (key bits 30..17) per scope: LDS histograms flushed to a global one.
+//            Scopes from 4M elements on are only sampled: one 16384-element tile of every aligned group
+//            of `stride`, at a hashed position.  The work is a list of slots shared evenly by the workgroups
+//   select0  per scope: bracket [lo, hi) that holds the k-th key - exactly one digit-0 bin when every
+//            element was counted; when the scope was sampled, the keys inside a confidence band around
+//            the estimated rank, its two ends interpolated inside their bins.  Also the scope's tie key
+//            (a key that very many in-bracket samples share, e.g. the zeros of a pruned model) and the
+//            layout of digit 1 over the bracket
 //   emit     one pass over the weights, one workgroup per 4096-element tile: mask bit = key >= hi,
-//            a compare's lane mask being the mask word; elements with lo <= key < hi are
-//            undecided: their composites go to the tile's record, with the tile's count of kept
-//            elements.  No atomics
-//   count1   from the records: digit-1 histogram of the undecided elements and kept counts per scope
+//            a compare's lane mask being the mask word; elements with lo <= key < hi are undecided:
+//            their composites go to the tile's record - except those with the tie key, which are
+//            counted per tile - and the tile's counts to its header.  No atomics
+//   count1   from the headers and records: digit-1 histogram of the undecided elements, kept and tie
+//            counts per scope
 //   select1  per scope: checks that the bracket did hold the k-th key (always true for exact
 //            counts), then the digit-1 bin b1 of the k-th undecided element and its rank inside
 //   (retry)  if a sampled bracket missed, hist0/select0/emit/count1/select1 run again with full
-//            counts; otherwise those five launches return at once
+//            counts and whole bins; otherwise those five launches return at once
 //   small    scopes of at most 32768 elements take no part in the above: one workgroup each selects
 //            from LDS and writes the scope's mask bits
 //   compact2 undecided elements whose digit 1 is their scope's b1 -> match lists (a few hundred per scope)
 //   final    one workgroup per scope gathers its matches into LDS and resolves the remaining
-//            bits there -> C*
-//   fixup    undecided elements with composite >= C* get their mask bit set (atomic OR)
+//            bits there -> C*; if C* carries the tie key, its index part comes from the tiles' tie counts
+//   fixup    undecided elements with composite >= C* get their mask bit set (atomic OR); tiles that
+//            hold kept tie-key elements are read again for them
 //   scan     exclusive prefix sum of the mask-word popcounts (single pass, decoupled look-back)
 //
-// A tile that holds more undecided elements than its record takes (very many equal magnitudes) is
-// not listed: count1, compact2 and fixup read that tile's weights instead.  A scope with more than
-// 4096 matches is resolved by `final` from its weights.  Same results, slower.
+// A tile that holds more undecided elements than its record takes is not listed: count1, compact2 and
+// fixup read that tile's weights instead.  A scope with more than 4096 matches is resolved by `final`
+// from its weights.  Same results, slower; the status word tells (kDevSlowPath).
 #include <cstdlib>
 #include <type_traits>
 
@@ -591,11 +596,12 @@ __global__ __launch_bounds__(kDigit1Bins / 16) void select1_kernel(const SegDesc
 // until its last memory operation is acknowledged, and a returning atomic is the slowest of them.
 //
 // Undecided elements are rare for continuous weight distributions (~0.5 %).  Their composites go,
-// through a small per-wave LDS stage, into the tile's record: 128 u64 slots per tile, slot 0 the
-// header (kept-element count << 32 | listed entries), then the entries.  A tile that holds more
-// undecided elements than its record takes (very many equal magnitudes) is marked kRecWalk: the
-// kernels that consume the records then walk that tile's 4096 weights instead - the overflow is
-// local, every other tile keeps its list.
+// through a small per-wave LDS stage, into the tile's record: 128 u64 slots per tile.  The tile's header
+// (listed entries, kept elements, tie-key elements of its first and of its last scope: 16 bits each) goes
+// into a dense array of its own, so that the passes which need only headers read 8 bytes per tile.
+// Elements whose key is the scope's tie key are counted, not listed.  A tile that still holds more
+// undecided elements than its record takes is marked kRecWalk: the kernels that consume the records then
+// walk that tile's 4096 weights instead - the overflow is local, every other tile keeps its list.
 constexpr int kEmitBlock = 256;
 constexpr int kEmitWaves = kEmitBlock / 64;
 constexpr uint32_t kEmitLoads = 16;                                 // dword loads per lane per tile
@@ -645,13 +651,8 @@ __device__ __forceinline__ bool advance_scope(const SegDesc* __restrict__ seg, u
 // reads it: two wait states" rule of this chip, which the compiler cannot apply inside an asm statement.
 template <uint32_t U>
 __device__ __forceinline__ void set_lane_pair(u64 m, uint32_t& lo, uint32_t& hi) {
-#ifdef PAC_EMIT_CSELECT
-    lo = lane_id() == U ? (uint32_t)m : lo;
-    hi = lane_id() == U ? (uint32_t)(m >> 32) : hi;
-#else
     asm volatile("s_nop 1\n\tv_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
                  : "+v"(lo), "+v"(hi) : "s"((uint32_t)m), "s"((uint32_t)(m >> 32)), "n"(U));
-#endif
 }
 
 // f(std::integral_constant<uint32_t, U>) for U = 0 .. N-1, so that U is a constant where an asm operand needs one.

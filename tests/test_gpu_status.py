@@ -138,3 +138,52 @@ def test_build_mask_checks_its_own_count_on_the_device():
         assert k == nnz and np.array_equal(mask.cpu().numpy().view(np.uint64), em)
     finally:
         ctx.close()
+
+
+def _mask_equals_oracle(ctx, w, s):
+    n = w.numel()
+    mask, prefix, nnz = ctx.build_mask(w, [0, n], s)
+    torch.cuda.synchronize()
+    em, ep, k = oracle.build_mask(w.cpu().numpy(), [0, n], s)
+    assert nnz == k
+    assert np.array_equal(mask.cpu().numpy().view(np.uint64), em)
+    assert np.array_equal(prefix.cpu().numpy().view(np.uint32), ep)
+
+
+def test_informational_bits_name_the_slower_exact_path_that_ran():
+    """Two inputs built to leave the fast path: magnitudes constant over each 16384-element tile (a sample of
+    tiles then predicts the quantile badly: the sampled bracket misses and the full-count round runs), and two
+    neighbouring magnitudes with hundreds of thousands of elements each, cut inside the one that is not the tie
+    key (its elements exceed what the final selection holds in LDS, so the scope is resolved from its weights).
+    The masks are the oracle's either way; the status word says which path produced them, and no error bit."""
+    import paper_2505_18563_amd as pac
+    dev = torch.device("cuda", 0)
+    rng = np.random.default_rng(52)
+    tile, tiles = 16384, 1300
+    n = tiles * tile + 77
+    per_tile = (rng.random(tiles + 1) * 4.0 + 0.01).astype(np.float32)
+    w = torch.from_numpy(np.repeat(per_tile, tile)[:n].copy()).to(dev)
+    ctx = pac.PacContext(max_elems=n, device=0)
+    try:
+        seen = 0
+        for s in (0.3, 0.5, 0.77):
+            _mask_equals_oracle(ctx, w, s)
+            seen |= ctx.device_status(clear=True)
+        assert seen & pac.PAC_DEV_ERROR_MASK == 0, f"status {seen:#x}"
+        assert seen & pac.PAC_DEV_RETRY_TAKEN, f"no sampled bracket missed (status {seen:#x})"
+    finally:
+        ctx.close()
+
+    n = 1_000_003
+    u = torch.from_numpy(rng.random(n)).to(dev)
+    w = torch.full((n,), 1.0, device=dev)
+    w[u < 0.4] = float(np.nextafter(np.float32(1.0), np.float32(2.0)))
+    ctx = pac.PacContext(max_elems=n, device=0)
+    try:
+        _mask_equals_oracle(ctx, w, 0.8)            # the 200,001-st largest lies inside the 40 % group
+        st = ctx.device_status(clear=True)
+        assert st & pac.PAC_DEV_ERROR_MASK == 0, f"status {st:#x}"
+        assert st & pac.PAC_DEV_SLOW_PATH, f"the scope was not resolved from its weights (status {st:#x})"
+        assert ctx.device_status() == 0
+    finally:
+        ctx.close()
