@@ -103,6 +103,45 @@ def test_full_config4_gpt2_medium_shaped_bf16_w16():
     run_full(4)
 
 
+def test_full_config4_mask_of_the_pruned_model_and_of_a_constant_tensor():
+    """The weights a training loop holds after its first step: pruned positions set to exactly +0 by the
+    library's own fused update (Eq. 1 and 2), so 90 % of the 354,823,168 elements tie at zero; re-pruned at
+    the same sparsity, the same mask must come back, on the fast path.  Then one all-equal scope of the same
+    length, where the tie rule alone decides.  Masks and prefixes whole against the oracle."""
+    import paper_2505_18563_amd as pac
+    dev = torch.device("cuda", 0)
+    wl = make_workload(4, device=dev)
+    n = wl.n
+    sp = wl.sparsity_at(0)
+    ctx = pac.PacContext(max_elems=n, max_segments=1, device=0)
+    try:
+        mask, prefix, nnz = ctx.build_mask(wl.weights, wl.scope_offsets, sp)
+        compact = [ctx.compress(g, mask, prefix, nnz) for g in wl.grads[:2]]
+        red = ctx.reduce_local(compact, nnz)
+        w2 = wl.weights.clone()
+        pac.pac_decompress_update(ctx.handle, red, mask, prefix, 1e-3, w2, nnz)
+        torch.cuda.synchronize()
+        assert int((w2 == 0).sum()) >= n - nnz
+        print(f"[full] pruned C4 weights: {n - nnz} zeros of {n}", flush=True)
+        for label, w in (("pruned", w2), ("all-equal", torch.full((n,), 0.02, device=dev))):
+            m2, p2, k2 = ctx.build_mask(w, wl.scope_offsets, sp)
+            torch.cuda.synchronize()
+            st = ctx.device_status(clear=True)
+            em, ep, k = oracle.build_mask(w.cpu().numpy(), wl.scope_offsets, sp)
+            assert k2 == k == nnz
+            assert np.array_equal(m2.cpu().numpy().view(np.uint64), em), f"{label}: mask words differ"
+            assert np.array_equal(p2.cpu().numpy().view(np.uint32), ep), f"{label}: prefix differs"
+            assert st == 0, f"{label}: device status {st:#x} (an error bit, or a slow path)"
+            if label == "pruned":
+                assert np.array_equal(em, mask.cpu().numpy().view(np.uint64)), "re-pruning the pruned model moved the mask"
+            print(f"[full]   {label}: mask and prefix equal, status 0", flush=True)
+            del w, m2, p2, em, ep
+    finally:
+        ctx.close()
+        del wl
+        torch.cuda.empty_cache()
+
+
 def test_full_config5_decoder_1p3b_per_layer_schedule_all_eight_workers():
     """1,315,723,264 elements, 292 prune scopes (the large ones sampled), every sparsity of the schedule,
     all 8 workers: 24 gathers, three 8-way fp32 sums of up to 657,861,632 elements, three scatters."""
