@@ -245,7 +245,7 @@ __device__ __forceinline__ u32x4 gather_chunk<uint16_t>(const uint16_t* p, uint3
 }
 
 template <typename T, int U>
-__global__ __launch_bounds__(kPackBlock) void decompress_tile_kernel(const T* __restrict__ compact, uint32_t nnz,
+__global__ __launch_bounds__(kPackBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void decompress_tile_kernel(const T* __restrict__ compact, uint32_t nnz,
                                                                      const unsigned long long* __restrict__ mask,
                                                                      const uint32_t* __restrict__ prefix,
                                                                      u32x4* __restrict__ dense, uint32_t n,
@@ -278,8 +278,10 @@ __global__ __launch_bounds__(kPackBlock) void decompress_tile_kernel(const T* __
 
     const uint32_t w0 = tile * G::kWords;
     const uint32_t w1 = w0 + G::kWords;
+    // both bounds in one round trip: the second index is clamped, not branched on
     const uint32_t s0 = prefix[w0];
-    const uint32_t s1 = w1 < words ? prefix[w1] : nnz;
+    const uint32_t s1_read = prefix[w1 < words ? w1 : words - 1u];
+    const uint32_t s1 = w1 < words ? s1_read : nnz;
     // Inconsistent metadata: read nothing, the tile's outputs become zero, the status word says so.
     const bool sane = s0 <= s1 && s1 <= nnz && s1 - s0 <= G::kElems;
     if (lane == 0) {
@@ -290,18 +292,35 @@ __global__ __launch_bounds__(kPackBlock) void decompress_tile_kernel(const T* __
     const uint32_t ph = phase_of(compact + s0);
     T* my = stage[wave];
 
-    // compact [s0, s1) -> LDS [ph, ph + count)
+    // compact [s0, s1) -> LDS [ph, ph + count): an element-wise head and tail, 16-byte chunks between them.
+    // All loads are issued before the first is used: a loop of load-then-store trips would cost one memory
+    // round trip per trip (up to NB of them for a dense tile).
     if (count != 0) {
+        constexpr int NB = U + 1;
         const T* gbase = compact + s0 - ph;
         const uint32_t a = ph, b = ph + count;
         uint32_t h_end = (a + E - 1u) & ~(E - 1u);
         if (h_end > b) h_end = b;
-        if (lane < h_end - a) my[a + lane] = gbase[a + lane];
-        for (uint32_t c = h_end / E + lane; c < b / E; c += 64)
-            *reinterpret_cast<u32x4*>(my + c * E) = *reinterpret_cast<const u32x4*>(gbase + c * E);
         uint32_t t0 = b & ~(E - 1u);
         if (t0 < h_end) t0 = h_end;
-        if (lane < b - t0) my[t0 + lane] = gbase[t0 + lane];
+        const uint32_t c_begin = h_end / E, c_end = b / E;
+        u32x4 r[NB];
+        T head = 0, tail = 0;
+        if (lane < h_end - a) head = gbase[a + lane];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const uint32_t c = c_begin + lane + 64u * (uint32_t)i;
+            r[i] = (u32x4){0, 0, 0, 0};
+            if (c < c_end) r[i] = *reinterpret_cast<const u32x4*>(gbase + c * E);
+        }
+        if (lane < b - t0) tail = gbase[t0 + lane];
+        if (lane < h_end - a) my[a + lane] = head;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const uint32_t c = c_begin + lane + 64u * (uint32_t)i;
+            if (c < c_end) *reinterpret_cast<u32x4*>(my + c * E) = r[i];
+        }
+        if (lane < b - t0) my[t0 + lane] = tail;
     }
     wave_lds_sync();
 
@@ -374,7 +393,7 @@ struct UpdateTile {
 };
 
 template <typename T, int U>
-__global__ __launch_bounds__(kPackBlock) void update_tile_kernel(const T* __restrict__ compact, uint32_t nnz,
+__global__ __launch_bounds__(kPackBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void update_tile_kernel(const T* __restrict__ compact, uint32_t nnz,
                                                                  const unsigned long long* __restrict__ mask,
                                                                  const uint32_t* __restrict__ prefix, float alpha,
                                                                  u32x4* __restrict__ weights, uint32_t n,
@@ -410,8 +429,10 @@ __global__ __launch_bounds__(kPackBlock) void update_tile_kernel(const T* __rest
 
     const uint32_t w0 = tile * G::kWords;
     const uint32_t w1 = w0 + G::kWords;
+    // both bounds in one round trip: the second index is clamped, not branched on
     const uint32_t s0 = prefix[w0];
-    const uint32_t s1 = w1 < words ? prefix[w1] : nnz;
+    const uint32_t s1_read = prefix[w1 < words ? w1 : words - 1u];
+    const uint32_t s1 = w1 < words ? s1_read : nnz;
     // Inconsistent metadata: read no compact value, kept weights of the tile stay as they are.
     const bool sane = s0 <= s1 && s1 <= nnz && s1 - s0 <= G::kElems;
     if (lane == 0) {
@@ -422,17 +443,35 @@ __global__ __launch_bounds__(kPackBlock) void update_tile_kernel(const T* __rest
     const uint32_t ph = phase_of(compact + s0);
     T* my = stage[wave];
 
+    // compact [s0, s1) -> LDS [ph, ph + count): an element-wise head and tail, 16-byte chunks between them.
+    // All loads are issued before the first is used: a loop of load-then-store trips would cost one memory
+    // round trip per trip (up to NB of them for a dense tile).
     if (count != 0) {
+        constexpr int NB = (int)(G::kElems / EC / 64) + 1;
         const T* gbase = compact + s0 - ph;
         const uint32_t a = ph, b = ph + count;
         uint32_t h_end = (a + EC - 1u) & ~(EC - 1u);
         if (h_end > b) h_end = b;
-        if (lane < h_end - a) my[a + lane] = gbase[a + lane];
-        for (uint32_t c = h_end / EC + lane; c < b / EC; c += 64)
-            *reinterpret_cast<u32x4*>(my + c * EC) = *reinterpret_cast<const u32x4*>(gbase + c * EC);
         uint32_t t0 = b & ~(EC - 1u);
         if (t0 < h_end) t0 = h_end;
-        if (lane < b - t0) my[t0 + lane] = gbase[t0 + lane];
+        const uint32_t c_begin = h_end / EC, c_end = b / EC;
+        u32x4 r[NB];
+        T head = 0, tail = 0;
+        if (lane < h_end - a) head = gbase[a + lane];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const uint32_t c = c_begin + lane + 64u * (uint32_t)i;
+            r[i] = (u32x4){0, 0, 0, 0};
+            if (c < c_end) r[i] = *reinterpret_cast<const u32x4*>(gbase + c * EC);
+        }
+        if (lane < b - t0) tail = gbase[t0 + lane];
+        if (lane < h_end - a) my[a + lane] = head;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const uint32_t c = c_begin + lane + 64u * (uint32_t)i;
+            if (c < c_end) *reinterpret_cast<u32x4*>(my + c * EC) = r[i];
+        }
+        if (lane < b - t0) my[t0 + lane] = tail;
     }
     wave_lds_sync();
 
