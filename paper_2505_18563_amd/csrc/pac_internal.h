@@ -11,8 +11,8 @@ namespace pac {
 // the 63-bit composite (key << 32) | (0xFFFFFFFF - flat_index): larger composite = kept first,
 // i.e. |w| descending, flat index ascending.  The selection finds the composite C* of the k-th
 // element in three steps:
-//   bracket: a key range [lo, hi) that holds the k-th key, made of whole bins of digit 0
-//            (key bits 30..17) taken from a histogram over all, or a sample of, the scope's elements
+//   bracket: a key range [lo, hi) that holds the k-th key, from a histogram of digit 0 (key bits 30..17)
+//            over all of the scope's elements (one whole bin) or over a sample of them (a rank band)
 //   tie key: if one key holds a visible share of the bracket's elements (the zeros of an already pruned
 //            model, a constant tensor), its elements are not listed one by one: every tile only counts
 //            them, and their flat order decides among them at the end
@@ -142,13 +142,12 @@ struct MaskScratch {
 
 // Launchers (defined in pac_mask.hip / pac_pack.hip).  All enqueue on `stream` and return the
 // first launch error.
-// `sampled_elems`: elements the first histogram pass visits (sum over scopes of length / stride).
-// `any_sampled`: some scope has a stride above 1.  `max_tiny` / `max_small`: length of the longest small scope of at most kTinyScope elements / of any
-// length in the table (0 = none).  `table_changed`: the scope table on the device is not the one of
-// the previous call.
-constexpr uint32_t kTinyScope = 4096;
+// `slots0` / `slots1`: work items of the sampled and of the full histogram pass (sums of hist_slots() over
+// the table).  `any_sampled`: some scope has a stride above 1.  `max_tiny` / `max_small`: length of the
+// longest small scope of at most kTinyScope elements / of any length in the table (0 = none).
 // `fresh_table`: s.tile_scope has not been filled for the table in s.seg yet.  `expect_total`: the sum of
 // the scopes' keep counts (the scan raises kDevCountMismatch if the mask holds another number of bits).
+constexpr uint32_t kTinyScope = 4096;
 hipError_t launch_build_mask(const MaskScratch& s, const float* d_weights, uint32_t n, uint32_t nseg,
                              uint32_t slots0, uint32_t slots1, bool any_sampled, uint32_t max_tiny, uint32_t max_small,
                              bool fresh_table, unsigned long long* d_mask, uint32_t* d_prefix,
