@@ -93,3 +93,32 @@ def test_per_tensor_keep_totals_of_the_configurations(pac):
         assert flat_size(specs) == int(n)
         assert sum(pac.pac_keep_count(t.numel, float(s)) for t in specs) == int(total)
         assert sum(oracle.keep_count(t.numel, float(s)) for t in specs) == int(total)
+
+
+def test_bench_refuses_more_than_one_gpu_before_touching_a_device():
+    """The benchmark is a one-GPU program: --gpus above 1 ends with a message and a non-zero status, on a
+    machine without a GPU as well (it decides before anything initialises a device)."""
+    import subprocess
+    import sys
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert p.returncode != 0
+    assert "ONE GPU" in (p.stdout + p.stderr)
+    assert not any(line.startswith("{") for line in p.stdout.splitlines())
+
+
+def test_committed_traffic_summary_is_what_the_bench_line_quotes():
+    """roofline.traffic comes from the committed counter summary: the file must carry the figure, within a few
+    percent of the kernel's algorithmic bytes (a summary of some other kernel or workload would not be)."""
+    sys_path_bench = os.path.join(ROOT, "bench.py")
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_for_test", sys_path_bench)
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    t = bench.measured_traffic(bench.HEADLINE)
+    assert t is not None
+    n, k = 354823168, 35482317
+    algorithmic = 2 * n + 3 * ((n + 63) // 64) * 4 + 2 * k      # bf16 gradient + mask and prefix words + compact buffer
+    assert algorithmic == 847140314
+    assert 1.0 <= t / algorithmic < 1.03
+    assert bench.measured_traffic(3) is None
