@@ -651,14 +651,14 @@ __global__ __launch_bounds__(kBlock) void reduce_scalar_kernel(WorkerPtrs bufs, 
 // single add per further worker: the order and the arithmetic of reduce_vec_kernel), and only the final
 // sums of the kept elements go through the LDS staging area into the reduced buffer, as in
 // compress_tile_kernel.  Mask words and prefix entries are read once per tile instead of once per worker.
-// Tiles of 4096 elements (64 mask words): 2 chunks per lane for bf16, 4 for fp32; the loads of 4 workers
-// are in flight together.
+// A lane takes U chunks and has the loads of G workers in flight together: bf16 2 chunks x 4 workers (tiles
+// of 4096 elements), fp32 1 chunk x up to 16 workers (tiles of 1024 elements).
 template <typename T>
 struct FusedShape;
 template <>
 struct FusedShape<uint16_t> { static constexpr int U = 2, G = 4; };   // measured: 6.3 TB/s on 16 bf16 streams; 4 x 4 and 2 x 8 the same, 1 x 8 slower
 template <>
-struct FusedShape<uint32_t> { static constexpr int U = 4, G = 4; };   // measured: 4 x 4 5.6 TB/s on 8 fp32 streams at s = 0.5, 4 x 2 5.1
+struct FusedShape<uint32_t> { static constexpr int U = 1, G = 16; };  // measured on 8 fp32 streams: 1 x 16 5.8-6.2 TB/s; 1 x 8 2 % less; 4 x 4 and 2 x 4 up to 10 % less
 
 template <typename T>
 struct FusedAcc;
